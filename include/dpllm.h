@@ -1,0 +1,137 @@
+/*
+ * dpllm.h — C boundary of the MI355X (gfx950) DP-LLM decode hot path.
+ *
+ * The library serves one multi-scale ("any-precision") weight-only-quantised model:
+ * every linear keeps a parent p-bit code per weight, stored as p bitplanes, and a
+ * per-row table of 2^k fp16 centroids for every k <= p, so that the k-bit model is
+ * read from the top k planes only (paper Sec. 2.2: variants of 3..n bits overlaid in
+ * the memory of one n-bit model).  Each linear carries a precision selector (paper
+ * Sec. 3 and Sec. 5.1) that estimates the relative error ||(W_h - W_l) x|| from the
+ * current input and picks h when the estimate exceeds the layer's threshold T, else l.
+ *
+ * Conventions
+ *   - Every function returns DPLLM_OK (0) or a negative DPLLM_E* code; nothing throws
+ *     or aborts.  dpllm_last_error() gives the text of the last failure on a model.
+ *   - "host" / "device" on a pointer says where the memory lives.  The caller owns all
+ *     device memory it passes in (weight arena, G, x, y, k, e) and keeps it alive while
+ *     the model refers to it; the library owns only a small selector workspace that
+ *     dpllm_model_create allocates and dpllm_model_destroy frees.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work
+ *     is enqueued on it; only dpllm_load_linear synchronises it.
+ *   - One model may be driven from one stream at a time (the selector workspace is
+ *     shared by the calls of a model).
+ *   - fp16 values cross the boundary as IEEE binary16 bit patterns (uint16_t).
+ *
+ * Canonical host layout of a linear with `out` rows and `in` columns (in % 32 == 0):
+ *   planes : uint32_t [p][out][in/32]; plane 0 = most significant bit of the p-bit
+ *            code; column c is bit (c % 32) of word c / 32.
+ *   luts   : luts[k - kmin] -> uint16_t [out][2^k] for k = kmin..p; the k-bit code of a
+ *            weight is the top k bits of its p-bit code.
+ * The library re-tiles the planes into a private, plane-separable device layout inside
+ * the caller's arena; dpllm_debug_unpack returns canonical codes for checking it.
+ */
+#ifndef DPLLM_H
+#define DPLLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DPLLM_OK 0
+#define DPLLM_EINVAL (-1) /* null pointer, bad id, bad flag, NaN threshold            */
+#define DPLLM_ESHAPE (-2) /* in % 32 != 0, out < 1, batch outside [1, DPLLM_MAX_BATCH] */
+#define DPLLM_ERANGE (-3) /* bitwidth outside [kmin, p] or p outside [1, 8]           */
+#define DPLLM_ESTATE (-4) /* linear not loaded, selector not set, arena too small     */
+#define DPLLM_EHIP (-5)   /* a HIP runtime call failed                                 */
+
+#define DPLLM_MAX_BITS 8
+#define DPLLM_MAX_BATCH 8
+#define DPLLM_MAX_PAIRS 4   /* (l,h) candidate pairs kept per linear                    */
+#define DPLLM_MAX_RANK 1024 /* projection rank r                                        */
+
+#define DPLLM_SEL_NONE 0   /* no estimator: always l                                     */
+#define DPLLM_SEL_PROJ 1   /* random projection: e = ||G x||_2      (paper Sec. 5.1)    */
+#define DPLLM_SEL_LINREG 2 /* linear regression: e = alpha ||x||_2 + beta (Sec. 5.1)    */
+
+typedef struct dpllm_model dpllm_model; /* opaque host object */
+
+/* Creates a model with room for n_linears linears (ids 0..n_linears-1), on the current
+ * HIP device.  *out receives the handle.  Errors: EINVAL, EHIP. */
+int dpllm_model_create(dpllm_model** out, int n_linears);
+
+/* Frees the handle and the library's workspace.  Caller-owned device memory is not
+ * touched.  NULL is accepted. */
+void dpllm_model_destroy(dpllm_model* m);
+
+/* Text of the last error on m (owned by m, valid until the next failing call). */
+const char* dpllm_last_error(const dpllm_model* m);
+
+/* Bytes of device arena one linear needs (planes + tables, 256-byte aligned parts).
+ * Errors: EINVAL (bytes NULL), ESHAPE, ERANGE. */
+int dpllm_linear_device_bytes(int out, int in, int p, int kmin, size_t* bytes);
+
+/* "Load a parent p-bit bitplane model with per-row LUTs for every k <= p" (Sec. 2.2).
+ * Copies linear `id` from the canonical layout into dev_arena (device, caller-owned,
+ * 256-byte aligned, >= dpllm_linear_device_bytes) in the private device layout.
+ * src_on_device = 0: planes and every luts[i] are host pointers;
+ * src_on_device = 1: they are device pointers (the array `luts` itself is always host).
+ * Synchronises `stream` before returning.  Reloading an id replaces it and drops its
+ * selectors.  Errors: EINVAL, ESHAPE, ERANGE, ESTATE (arena too small), EHIP. */
+int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin,
+                      const uint32_t* planes, const uint16_t* const* luts, int src_on_device,
+                      void* dev_arena, size_t arena_bytes, void* stream);
+
+/* Attaches the precision selector of candidate pair (l, h), kmin <= l <= h <= p, to a
+ * loaded linear and makes it the active pair (Sec. 3: two candidate precisions per
+ * layer; Sec. 5.1: one G per pair).  kind = DPLLM_SEL_PROJ: G_dev is a device pointer
+ * to fp16 [r][in] (row-major, borrowed), G = A (W_h - W_l) precomputed by the caller,
+ * 1 <= r <= DPLLM_MAX_RANK.  kind = DPLLM_SEL_LINREG uses alpha, beta.  kind =
+ * DPLLM_SEL_NONE needs l == h.  T may be +inf (always l) or -inf (always h), not NaN.
+ * Setting an existing pair replaces it.  Errors: EINVAL, ERANGE, ESTATE. */
+int dpllm_set_selector(dpllm_model* m, int id, int l, int h, int kind, const void* G_dev, int r,
+                       float alpha, float beta, float T);
+
+/* Replaces the threshold of an existing pair (Algorithm 1: one threshold list per
+ * target precision).  Errors: EINVAL (NaN), ESTATE (pair not set). */
+int dpllm_set_threshold(dpllm_model* m, int id, int l, int h, float T);
+
+/* Chooses which of a linear's pairs dpllm_decode_step uses.  Errors: ESTATE. */
+int dpllm_set_active_pair(dpllm_model* m, int id, int l, int h);
+
+/* "Estimate the relative error for (layer, x)" (Sec. 5.1) and select (Sec. 3):
+ * e_dev[0] = estimate (fp32, rounded from the fp64 the decision is taken in),
+ * k_dev[0] = h if estimate > T else l.  x_dev: device fp16 [in].  e_dev, k_dev: device.
+ * Errors: EINVAL, ESTATE (pair not set), EHIP. */
+int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, float* e_dev,
+                   int32_t* k_dev, void* stream);
+
+/* "Run the GEMV at bitwidth k": y[b][o] = sum_c LUT_k[o][code_k(o,c)] * x[b][c], fp32
+ * accumulation, fp16 result.  k >= 0: that bitwidth.  k < 0: the bitwidth is read on the
+ * device from k_dev[0], which must hold l or h of the linear's active pair (the hand-over
+ * from dpllm_estimate without a host round trip).  x_dev: device fp16 [B][in]; y_dev:
+ * device fp16 [B][out]; 1 <= B <= DPLLM_MAX_BATCH; one bitwidth serves the whole batch.
+ * Errors: EINVAL, ESHAPE, ERANGE, ESTATE, EHIP. */
+int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* x_dev, void* y_dev,
+               int B, void* stream);
+
+/* "Run a whole decode step under per-layer thresholds" (Sec. 3, every linear operation
+ * of every Transformer block carries a selector): for id = 0..n_linears-1 in order,
+ * estimate on xs[id] with the active pair, then the GEMV at the selected bitwidth into
+ * ys[id], batch 1, all on `stream` with no host synchronisation.  xs, ys: host arrays of
+ * n_linears device pointers (fp16 [in_id], fp16 [out_id]).  k_dev, e_dev: device arrays
+ * of n_linears entries receiving every linear's bitwidth and estimate.  Results equal
+ * those of running the linears one after another.  Errors: EINVAL, ESTATE, EHIP. */
+int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev,
+                      float* e_dev, void* stream);
+
+/* Parity aid: writes the canonical k-bit codes of linear `id`, uint8 [out][in], read back
+ * from the private device layout, to idx_dev (device).  Errors: EINVAL, ERANGE, ESTATE, EHIP. */
+int dpllm_debug_unpack(dpllm_model* m, int id, int k, uint8_t* idx_dev, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPLLM_H */

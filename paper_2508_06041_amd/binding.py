@@ -1,0 +1,162 @@
+"""ctypes binding with the same names as include/dpllm.h.  Argument marshalling only.
+
+Tensors are torch tensors used purely as device memory: the binding passes data_ptr() and the
+current HIP stream to the C functions.  Functions raise DpllmError on a negative return code.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdpllm.so")
+
+DPLLM_OK, DPLLM_EINVAL, DPLLM_ESHAPE, DPLLM_ERANGE, DPLLM_ESTATE, DPLLM_EHIP = 0, -1, -2, -3, -4, -5
+DPLLM_SEL_NONE, DPLLM_SEL_PROJ, DPLLM_SEL_LINREG = 0, 1, 2
+DPLLM_MAX_BATCH = 8
+
+SYMBOLS = ["dpllm_model_create", "dpllm_model_destroy", "dpllm_last_error", "dpllm_linear_device_bytes",
+           "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair",
+           "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_debug_unpack"]
+
+
+class DpllmError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("dpllm error %d: %s" % (code, msg))
+        self.code = code
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libdpllm.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no fallback path)")
+    L = C.CDLL(_LIB_PATH)
+    vp, i32, f32, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+    L.dpllm_model_create.argtypes = [C.POINTER(vp), i32]
+    L.dpllm_model_destroy.argtypes = [vp]
+    L.dpllm_model_destroy.restype = None
+    L.dpllm_last_error.argtypes = [vp]
+    L.dpllm_last_error.restype = C.c_char_p
+    L.dpllm_linear_device_bytes.argtypes = [i32, i32, i32, i32, C.POINTER(sz)]
+    L.dpllm_load_linear.argtypes = [vp, i32, i32, i32, i32, i32, vp, C.POINTER(vp), i32, vp, sz, vp]
+    L.dpllm_set_selector.argtypes = [vp, i32, i32, i32, i32, vp, i32, f32, f32, f32]
+    L.dpllm_set_threshold.argtypes = [vp, i32, i32, i32, f32]
+    L.dpllm_set_active_pair.argtypes = [vp, i32, i32, i32]
+    L.dpllm_estimate.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
+    L.dpllm_gemv.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp]
+    L.dpllm_decode_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
+    L.dpllm_debug_unpack.argtypes = [vp, i32, i32, vp, vp]
+    return L
+
+
+lib = _load()
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr())
+
+
+def _check(model, rc):
+    if rc != 0:
+        msg = lib.dpllm_last_error(model).decode() if model else ""
+        raise DpllmError(rc, msg)
+
+
+def dpllm_linear_device_bytes(out, in_, p, kmin):
+    n = C.c_size_t(0)
+    rc = lib.dpllm_linear_device_bytes(out, in_, p, kmin, C.byref(n))
+    if rc != 0:
+        raise DpllmError(rc, "dpllm_linear_device_bytes(%d,%d,%d,%d)" % (out, in_, p, kmin))
+    return n.value
+
+
+class Model:
+    """Owns the C handle and the torch tensors used as device arenas."""
+
+    def __init__(self, n_linears):
+        h = C.c_void_p()
+        rc = lib.dpllm_model_create(C.byref(h), n_linears)
+        if rc != 0:
+            raise DpllmError(rc, "dpllm_model_create")
+        self.h = h
+        self.n = n_linears
+        self.arenas = {}
+        self.keep = {}
+        self.shapes = {}
+
+    def close(self):
+        if self.h:
+            lib.dpllm_model_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        self.close()
+
+    def dpllm_load_linear(self, id, planes, luts, kmin):
+        """planes: int32/uint32 [p][out][in/32] (numpy or torch, host or device);
+        luts: dict or list of fp16/uint16 [out][2^k] for k = kmin..p."""
+        import numpy as np
+        if isinstance(planes, np.ndarray):
+            planes = torch.from_numpy(planes.view(np.int32))
+        p, out, nw = planes.shape
+        if isinstance(luts, dict):
+            luts = [luts[k] for k in range(kmin, p + 1)]
+        luts = [torch.from_numpy(t.view(np.int16)) if isinstance(t, np.ndarray) else t for t in luts]
+        on_dev = planes.is_cuda
+        luts = [(t.cuda() if on_dev else t.cpu()).contiguous() for t in luts]
+        planes = planes.contiguous()
+        nbytes = dpllm_linear_device_bytes(out, nw * 32, p, kmin)
+        arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        arr = (C.c_void_p * len(luts))(*[t.data_ptr() for t in luts])
+        rc = lib.dpllm_load_linear(self.h, id, out, nw * 32, p, kmin, _ptr(planes), arr, 1 if on_dev else 0,
+                                   _ptr(arena), nbytes, _stream())
+        _check(self.h, rc)
+        self.arenas[id] = arena
+        self.shapes[id] = (out, nw * 32, p, kmin)
+
+    def dpllm_set_selector(self, id, l, h, kind, G=None, alpha=0.0, beta=0.0, T=float("inf")):
+        r = 0
+        if G is not None:
+            G = G.contiguous()
+            assert G.is_cuda and G.dtype == torch.float16
+            r = G.shape[0]
+            self.keep[(id, l, h)] = G
+        _check(self.h, lib.dpllm_set_selector(self.h, id, l, h, kind, _ptr(G), r, alpha, beta, T))
+
+    def dpllm_set_threshold(self, id, l, h, T):
+        _check(self.h, lib.dpllm_set_threshold(self.h, id, l, h, T))
+
+    def dpllm_set_active_pair(self, id, l, h):
+        _check(self.h, lib.dpllm_set_active_pair(self.h, id, l, h))
+
+    def dpllm_estimate(self, id, l, h, x, e_out=None, k_out=None):
+        e_out = torch.empty(1, dtype=torch.float32, device="cuda") if e_out is None else e_out
+        k_out = torch.empty(1, dtype=torch.int32, device="cuda") if k_out is None else k_out
+        _check(self.h, lib.dpllm_estimate(self.h, id, l, h, _ptr(x), _ptr(e_out), _ptr(k_out), _stream()))
+        return e_out, k_out
+
+    def dpllm_gemv(self, id, k, x, y=None, k_dev=None):
+        """k >= 0: fixed bitwidth.  k < 0: read the bitwidth from k_dev on the device."""
+        out = self.shapes.get(id, (1,))[0]   # an unknown id is reported by the library
+        B = 1 if x.dim() == 1 else x.shape[0]
+        if y is None:
+            y = torch.empty((out,) if x.dim() == 1 else (B, out), dtype=torch.float16, device="cuda")
+        _check(self.h, lib.dpllm_gemv(self.h, id, k, _ptr(k_dev), _ptr(x), _ptr(y), B, _stream()))
+        return y
+
+    def dpllm_decode_step(self, xs, ys, k_out, e_out):
+        xa = (C.c_void_p * self.n)(*[t.data_ptr() for t in xs])
+        ya = (C.c_void_p * self.n)(*[t.data_ptr() for t in ys])
+        _check(self.h, lib.dpllm_decode_step(self.h, xa, ya, _ptr(k_out), _ptr(e_out), _stream()))
+
+    def dpllm_debug_unpack(self, id, k):
+        out, in_, _, _ = self.shapes.get(id, (1, 32, 0, 0))
+        idx = torch.empty((out, in_), dtype=torch.uint8, device="cuda")
+        _check(self.h, lib.dpllm_debug_unpack(self.h, id, k, _ptr(idx), _stream()))
+        return idx

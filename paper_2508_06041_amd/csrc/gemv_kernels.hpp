@@ -1,0 +1,81 @@
+// Any-precision GEMV kernels: y = W_k x with W_k[o][c] = LUT_k[o][code_p(o,c) >> (p - k)], reading
+// the top k bitplanes only (paper Sec. 3: the linear operation of a decode step is a GEMV;
+// Sec. 2.2: the k-bit model is overlaid in the parent's memory).
+#pragma once
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace dpllm {
+
+struct GemvArgs {
+  const uint4* planes;       // device planes, plane b at planes + b * plane_stride_u4
+  size_t plane_stride_u4;
+  const uint16_t* lut_a;     // table of bitwidth ka, [nrq*4][2^ka]
+  const uint16_t* lut_b;     // table of bitwidth kb (dynamic selection) or nullptr
+  int ka, kb;
+  const int32_t* k_dev;      // nullptr: use ka; else *k_dev in {ka, kb}
+  const uint16_t* x;         // fp16 [B][in]
+  uint16_t* y;               // fp16 [B][out]
+  int out, in, ncw, nrq;
+};
+
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
+}
+
+// Plain kernel: one wave per row quad, one code bit at a time.  Serves every (k, B).
+template <int B>
+__global__ void __launch_bounds__(256) gemv_plain_kernel(GemvArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rq = blockIdx.x * 4 + wave;
+  if (rq >= a.nrq) return;
+  int k = a.ka;
+  const uint16_t* lut = a.lut_a;
+  if (a.k_dev != nullptr) {
+    int kd = *a.k_dev;
+    if (kd == a.kb) { k = a.kb; lut = a.lut_b; }
+  }
+  float acc[4][B];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int b = 0; b < B; ++b) acc[r][b] = 0.f;
+  for (int cw = lane; cw < a.ncw; cw += 64) {
+    uint4 w[8];
+    for (int b = 0; b < k; ++b) w[b] = a.planes[(size_t)b * a.plane_stride_u4 + (size_t)rq * a.ncw + cw];
+    for (int q = 0; q < 32; ++q) {
+      uint32_t code[4] = {0, 0, 0, 0};
+      for (int b = 0; b < k; ++b) {
+        int pos = (q - b) & 31;  // plane b keeps column q at bit q - b
+        code[0] = (code[0] << 1) | ((w[b].x >> pos) & 1u);
+        code[1] = (code[1] << 1) | ((w[b].y >> pos) & 1u);
+        code[2] = (code[2] << 1) | ((w[b].z >> pos) & 1u);
+        code[3] = (code[3] << 1) | ((w[b].w >> pos) & 1u);
+      }
+      float xv[B];
+#pragma unroll
+      for (int b = 0; b < B; ++b)
+        xv[b] = __half2float(__ushort_as_half(a.x[(size_t)b * a.in + cw * 32 + q]));
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float wv = __half2float(__ushort_as_half(lut[((size_t)(rq * 4 + r) << k) + code[r]]));
+#pragma unroll
+        for (int b = 0; b < B; ++b) acc[r][b] = fmaf(wv, xv[b], acc[r][b]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      float s = wave_sum_f32(acc[r][b]);
+      int o = rq * 4 + r;
+      if (lane == 0 && o < a.out) a.y[(size_t)b * a.out + o] = __half_as_ushort(__float2half_rn(s));
+    }
+}
+
+}  // namespace dpllm

@@ -1,0 +1,286 @@
+"""GPU parity: the HIP library, called through its C boundary, against the CPU oracle on the
+same seeded inputs.  Integer work (codes, bitwidth decisions) must be bit-exact; GEMV outputs
+must be within 2e-3 relative L2 (fp32 accumulation, fp16 result)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 2e-3          # tolerance of the GEMV output stated for this path
+DECISION_BAND = 1e-9   # decisions must agree wherever |e - T| exceeds this relative band
+
+
+@pytest.fixture(scope="module")
+def dp():
+    import paper_2508_06041_amd as dp
+    assert torch.cuda.is_available()
+    return dp
+
+
+def rel_l2(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    n = np.linalg.norm(ref)
+    return np.linalg.norm(got - ref) / (n if n > 0 else 1.0)
+
+
+def load(dp, lins):
+    model = dp.Model(len(lins))
+    for i, lin in enumerate(lins):
+        model.dpllm_load_linear(i, synth.planes_np(lin["planes"]),
+                                {k: synth.lut_np(v) for k, v in lin["luts"].items()}, lin["kmin"])
+    return model
+
+
+# ----------------------------------------------------------------------------- T1 codes
+@pytest.mark.parametrize("p", range(1, 9))
+def test_unpack_bit_exact_all_p_k(dp, p):
+    rng = np.random.default_rng(p)
+    for out, in_ in [(1, 32), (33, 96), (7, 2080), (130, 4096 + 32)]:
+        planes = rng.integers(0, 2 ** 32, size=(p, out, in_ // 32), dtype=np.uint32)
+        luts = {k: np.zeros((out, 1 << k), dtype=np.uint16) for k in range(1, p + 1)}
+        model = dp.Model(1)
+        model.dpllm_load_linear(0, planes, luts, 1)
+        ref_p = oracle.unpack(planes)
+        for k in range(1, p + 1):
+            got = model.dpllm_debug_unpack(0, k).cpu().numpy()
+            assert (got == oracle.index_k(ref_p, p, k)).all(), (p, k, out, in_)
+        model.close()
+
+
+def test_load_from_device_pointers_matches_host_load(dp):
+    lin = synth.make_linear(40, 160, 6, 3, seed=5)
+    a = load(dp, [lin])
+    b = dp.Model(1)
+    b.dpllm_load_linear(0, lin["planes"].cuda(), {k: v.cuda() for k, v in lin["luts"].items()}, 3)
+    x = synth.make_x(160, 1, seed=6)[0].cuda()
+    for k in range(3, 7):
+        assert torch.equal(a.dpllm_debug_unpack(0, k), b.dpllm_debug_unpack(0, k))
+        assert torch.equal(a.dpllm_gemv(0, k, x), b.dpllm_gemv(0, k, x))
+
+
+# ----------------------------------------------------------------------------- T3 GEMV
+TINY = [(2, 32, 4, 3), (7, 64, 8, 3), (33, 96, 5, 3), (5, 160, 3, 1), (257, 2048 + 64, 8, 3), (64, 11008, 6, 3)]
+
+
+@pytest.mark.parametrize("out,in_,p,kmin", TINY)
+def test_gemv_small_shapes_all_k(dp, out, in_, p, kmin):
+    lin = synth.make_linear(out, in_, p, kmin, seed=out + in_)
+    model = load(dp, [lin])
+    x = synth.make_x(in_, 1, seed=out)[0]
+    planes = synth.planes_np(lin["planes"])
+    for k in range(kmin, p + 1):
+        ref = oracle.gemv(planes, k, synth.lut_np(lin["luts"][k]), synth.lut_np(x))
+        got = model.dpllm_gemv(0, k, x.cuda()).float().cpu().numpy()
+        assert rel_l2(got, ref) <= REL_L2, (k, rel_l2(got, ref))
+    model.close()
+
+
+def test_gemv_special_inputs(dp):
+    lin = synth.make_linear(48, 256, 6, 3, seed=77)
+    model = load(dp, [lin])
+    planes = synth.planes_np(lin["planes"])
+    codes = oracle.unpack(planes)
+    for c in (0, 31, 32, 100, 255):       # x = e_c returns column c of W_k exactly
+        e = torch.zeros(256, dtype=torch.float16)
+        e[c] = 1.0
+        for k in (3, 6):
+            got = model.dpllm_gemv(0, k, e.cuda()).cpu().numpy()
+            lut = synth.to_np(lin["luts"][k])
+            assert (got == lut[np.arange(48), codes[:, c] >> (6 - k)]).all()
+    zero = torch.zeros(256, dtype=torch.float16, device="cuda")
+    assert (model.dpllm_gemv(0, 4, zero) == 0).all()
+    model.close()
+
+
+def test_gemv_config0_1024(dp):
+    lin = synth.make_linear(1024, 1024, 4, 3, seed=0)
+    x = synth.make_x(1024, 1, seed=0, outliers=False)[0]
+    model = load(dp, [lin])
+    for k in (3, 4):
+        ref = oracle.gemv(synth.planes_np(lin["planes"]), k, synth.lut_np(lin["luts"][k]), synth.lut_np(x))
+        got = model.dpllm_gemv(0, k, x.cuda()).float().cpu().numpy()
+        assert rel_l2(got, ref) <= REL_L2
+    model.close()
+
+
+@pytest.mark.parametrize("out,in_", [(4096, 4096), (11008, 4096), (4096, 11008)])
+def test_gemv_llama7b_shapes_k3_to_8(dp, out, in_):
+    lin = synth.make_linear(out, in_, 8, 3, seed=out * 7 + in_, device="cuda", keep_codes=False)
+    model = dp.Model(1)
+    model.dpllm_load_linear(0, lin["planes"], lin["luts"], 3)
+    x = synth.make_x(in_, 1, seed=3)[0]
+    planes = synth.planes_np(lin["planes"])
+    for k in range(3, 9):
+        ref = oracle.gemv(planes, k, synth.lut_np(lin["luts"][k]), synth.lut_np(x))
+        got = model.dpllm_gemv(0, k, x.cuda()).float().cpu().numpy()
+        assert rel_l2(got, ref) <= REL_L2, (k, rel_l2(got, ref))
+    model.close()
+
+
+@pytest.mark.parametrize("B", [2, 3, 4, 8])
+def test_gemv_small_batch(dp, B):
+    lin = synth.make_linear(260, 4096, 8, 3, seed=B)
+    model = load(dp, [lin])
+    X = synth.make_x(4096, B, seed=10 + B)
+    planes = synth.planes_np(lin["planes"])
+    for k in (3, 4, 5, 6):
+        ref = oracle.gemv(planes, k, synth.lut_np(lin["luts"][k]), synth.lut_np(X))
+        got = model.dpllm_gemv(0, k, X.cuda()).float().cpu().numpy()
+        assert got.shape == (B, 260)
+        assert rel_l2(got, ref) <= REL_L2
+    model.close()
+
+
+# ----------------------------------------------------------------------------- T4-T6 selector
+def test_estimate_matches_oracle_and_hands_k_over(dp):
+    lin = synth.make_linear(96, 4096 + 256, 5, 3, seed=21)
+    model = load(dp, [lin])
+    planes = synth.planes_np(lin["planes"])
+    for r in (1, 16, 64, 256):
+        G = synth.make_G(lin, 3, 4, r, seed=22 + r)
+        xs = synth.make_x(lin["in"], 6, seed=23)
+        est = [oracle.estimate(synth.lut_np(G), synth.lut_np(x)) for x in xs]
+        T = synth.nudge_threshold(float(np.median(est)), torch.tensor(est))
+        model.dpllm_set_selector(0, 3, 4, dp.DPLLM_SEL_PROJ, G=G.cuda(), T=T)
+        for x, e_ref in zip(xs, est):
+            e, k = model.dpllm_estimate(0, 3, 4, x.cuda())
+            k_ref = oracle.decide(e_ref, T, 3, 4)
+            assert abs(e_ref - T) > DECISION_BAND * max(abs(T), e_ref)
+            assert int(k) == k_ref
+            assert float(e) == float(np.float32(e_ref)) or math.isclose(float(e), e_ref, rel_tol=3e-7)
+            y = model.dpllm_gemv(0, -1, x.cuda(), k_dev=k)      # bitwidth read on the device
+            ref = oracle.gemv(planes, k_ref, synth.lut_np(lin["luts"][k_ref]), synth.lut_np(x))
+            assert rel_l2(y.float().cpu().numpy(), ref) <= REL_L2
+            assert torch.equal(y, model.dpllm_gemv(0, k_ref, x.cuda()))
+    model.close()
+
+
+def test_degenerate_thresholds_and_kinds(dp):
+    lin = synth.make_linear(64, 512, 6, 3, seed=31)
+    model = load(dp, [lin])
+    G = synth.make_G(lin, 4, 5, 64, seed=32).cuda()
+    x = synth.make_x(512, 1, seed=33)[0]
+    model.dpllm_set_selector(0, 4, 5, dp.DPLLM_SEL_PROJ, G=G, T=float("inf"))
+    assert int(model.dpllm_estimate(0, 4, 5, x.cuda())[1]) == 4
+    model.dpllm_set_threshold(0, 4, 5, float("-inf"))
+    assert int(model.dpllm_estimate(0, 4, 5, x.cuda())[1]) == 5
+    model.dpllm_set_threshold(0, 4, 5, -1.0)
+    assert int(model.dpllm_estimate(0, 4, 5, x.cuda())[1]) == 5
+    e_ref = oracle.estimate(synth.lut_np(G.cpu()), synth.lut_np(x))
+    model.dpllm_set_threshold(0, 4, 5, float(np.float32(e_ref)) * 2)
+    assert int(model.dpllm_estimate(0, 4, 5, x.cuda())[1]) == 4
+    # linear-regression estimator
+    alpha, beta = 0.375, 0.5
+    model.dpllm_set_selector(0, 3, 4, dp.DPLLM_SEL_LINREG, alpha=alpha, beta=beta, T=0.0)
+    e, k = model.dpllm_estimate(0, 3, 4, x.cuda())
+    assert math.isclose(float(e), oracle.linreg_estimate(synth.lut_np(x), alpha, beta), rel_tol=3e-7)
+    assert int(k) == 4
+    # no estimator: l == h
+    model.dpllm_set_selector(0, 6, 6, dp.DPLLM_SEL_NONE)
+    e, k = model.dpllm_estimate(0, 6, 6, x.cuda())
+    assert int(k) == 6 and float(e) == 0.0
+    model.close()
+
+
+def _step_model(dp, shapes, p, l, h, r, n_steps, seed, mode):
+    """Builds a model with one selector per linear; returns everything the comparison needs."""
+    lins, refs = [], []
+    model = dp.Model(len(shapes))
+    xs_by_in = {in_: synth.make_x(in_, n_steps, seed=seed + in_) for _, in_ in shapes}
+    for i, (out, in_) in enumerate(shapes):
+        lin = synth.make_linear(out, in_, p, 3, seed=seed + 13 * i)
+        G = synth.make_G(lin, l, h, r, seed=seed + 17 * i + 1)
+        est = synth.estimates_fp64(G, xs_by_in[in_])
+        if mode == "inf":
+            T = float("inf")
+        elif mode == "-inf":
+            T = float("-inf")
+        else:
+            T = synth.nudge_threshold(synth.quantile_threshold(est, 0.5), est, band=1e-6)
+        model.dpllm_load_linear(i, synth.planes_np(lin["planes"]),
+                                {k: synth.lut_np(v) for k, v in lin["luts"].items()}, 3)
+        model.dpllm_set_selector(i, l, h, dp.DPLLM_SEL_PROJ, G=G.cuda(), T=T)
+        refs.append({"planes": synth.planes_np(lin["planes"]),
+                     "luts": {k: synth.lut_np(v) for k, v in lin["luts"].items()},
+                     "selector": {"l": l, "h": h, "kind": 1, "G": synth.lut_np(G), "T": T}})
+        lins.append(lin)
+    return model, refs, xs_by_in
+
+
+@pytest.mark.parametrize("mode", ["mixed", "inf", "-inf"])
+def test_decode_step_matches_oracle(dp, mode):
+    shapes = [(128, 256), (128, 256), (64, 256), (128, 128), (320, 256), (320, 256), (256, 320)]
+    n_steps = 12
+    model, refs, xs_by_in = _step_model(dp, shapes, 5, 3, 4, 64, n_steps, seed=900, mode=mode)
+    n = len(shapes)
+    k_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(n, dtype=torch.float32, device="cuda")
+    seen = set()
+    for t in range(n_steps):
+        xs = [xs_by_in[in_][t].cuda() for _, in_ in shapes]
+        ys = [torch.empty(out, dtype=torch.float16, device="cuda") for out, _ in shapes]
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+        torch.cuda.synchronize()
+        ry, rk, re = oracle.decode_step(refs, [synth.lut_np(xs_by_in[in_][t]) for _, in_ in shapes])
+        for ref, e in zip(refs, re):
+            T = ref["selector"]["T"]
+            if np.isfinite(T):
+                assert abs(e - T) > DECISION_BAND * max(abs(T), e)
+        assert k_dev.cpu().numpy().tolist() == rk.tolist()
+        assert np.allclose(e_dev.cpu().numpy(), re, rtol=3e-7)
+        for y, r in zip(ys, ry):
+            assert rel_l2(y.float().cpu().numpy(), r) <= REL_L2
+        seen.update(rk.tolist())
+    assert seen == ({3, 4} if mode == "mixed" else {3} if mode == "inf" else {4})
+    model.close()
+
+
+# ----------------------------------------------------------------------------- T7 error paths
+def test_abi_error_paths(dp):
+    lin = synth.make_linear(8, 64, 4, 3, seed=1)
+    model = load(dp, [lin, lin])
+    x = torch.zeros(64, dtype=torch.float16, device="cuda")
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_gemv(0, 2, x)                      # below kmin
+    assert ei.value.code == dp.DPLLM_ERANGE
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_gemv(0, 5, x)                      # above p
+    assert ei.value.code == dp.DPLLM_ERANGE
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_gemv(5, 3, x)                      # bad id
+    assert ei.value.code == dp.DPLLM_EINVAL
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_gemv(0, 3, torch.zeros(9, 64, dtype=torch.float16, device="cuda"),
+                         y=torch.zeros(9, 8, dtype=torch.float16, device="cuda"))
+    assert ei.value.code == dp.DPLLM_ESHAPE
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_estimate(0, 3, 4, x)               # selector not set
+    assert ei.value.code == dp.DPLLM_ESTATE
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_set_selector(0, 3, 4, dp.DPLLM_SEL_PROJ, G=torch.zeros(4, 64, dtype=torch.float16, device="cuda"),
+                                 T=float("nan"))
+    assert ei.value.code == dp.DPLLM_EINVAL
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_gemv(0, -1, x)                     # dynamic k without k_dev
+    assert ei.value.code == dp.DPLLM_EINVAL
+    k_dev = torch.zeros(2, dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(2, dtype=torch.float32, device="cuda")
+    with pytest.raises(dp.DpllmError) as ei:           # decode step without selectors
+        model.dpllm_decode_step([x, x], [torch.zeros(8, dtype=torch.float16, device="cuda")] * 2, k_dev, e_dev)
+    assert ei.value.code == dp.DPLLM_ESTATE
+    empty = dp.Model(1)
+    with pytest.raises(dp.DpllmError) as ei:
+        empty.dpllm_gemv(0, 3, x)                      # not loaded
+    assert ei.value.code == dp.DPLLM_ESTATE
+    import ctypes as C
+    n = C.c_size_t(0)
+    assert dp.lib.dpllm_linear_device_bytes(8, 48, 4, 3, C.byref(n)) == dp.DPLLM_ESHAPE
+    model.close()
+    empty.close()
