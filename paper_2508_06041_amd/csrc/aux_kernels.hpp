@@ -5,6 +5,8 @@
 
 #include <cstdint>
 
+#include "layout_device.hpp"
+
 namespace dpllm {
 
 __device__ __forceinline__ uint32_t rotr32(uint32_t v, int s) { return __builtin_rotateright32(v, s); }
@@ -23,7 +25,7 @@ __global__ void retile_planes_kernel(const uint32_t* __restrict__ canon, uint4* 
   for (int r = 0; r < 4; ++r) {
     int o = rq * 4 + r;
     uint32_t v = (o < out) ? canon[((size_t)b * out + o) * ncw + cw] : 0u;
-    w[r] = rotr32(v, b);
+    w[r] = rotr32(permute_word(v), b);
   }
   dev[(size_t)b * plane_stride_u4 + e] = make_uint4(w[0], w[1], w[2], w[3]);
 }
@@ -49,7 +51,7 @@ __global__ void debug_unpack_kernel(const uint4* __restrict__ dev, size_t plane_
   for (int b = 0; b < p; ++b) {
     uint4 v = dev[(size_t)b * plane_stride_u4 + (size_t)rq * ncw + cw];
     uint32_t s = r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w;
-    w[b] = (s << b) | (b ? (s >> (32 - b)) : 0u);  // undo the rotation: canonical word
+    w[b] = unpermute_word((s << b) | (b ? (s >> (32 - b)) : 0u));  // undo rotation and permutation
   }
   for (int c = 0; c < 32; ++c) {
     uint32_t code = 0;

@@ -12,6 +12,7 @@
 
 #include "../../include/dpllm.h"
 #include "aux_kernels.hpp"
+#include "gemv_fast.hpp"
 #include "gemv_kernels.hpp"
 #include "layout.hpp"
 
@@ -132,7 +133,21 @@ int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t
   a.ncw = lin.L.ncw;
   a.nrq = lin.L.nrq;
   switch (B) {
-    case 1: launch_plain<1>(a, st); break;
+    case 1: {
+      GemvJob j;
+      j.arena = lin.arena;
+      j.x = (const uint16_t*)x;
+      j.y = (uint16_t*)y;
+      j.k_dev = k_dev;
+      j.plane_stride_u4 = (uint32_t)(lin.L.plane_bytes / 16);
+      j.lut_off_a = (uint32_t)lin.L.lut_offset[ka];
+      j.lut_off_b = (uint32_t)lin.L.lut_offset[kb];
+      j.ka = ka; j.kb = kb;
+      j.out = lin.L.out; j.ncw = lin.L.ncw; j.nrq = lin.L.nrq;
+      j.block_start = 0;
+      hipLaunchKernelGGL(gemv_one_kernel, dim3(lin.L.nrq), dim3(64), 0, st, j);
+      break;
+    }
     case 2: launch_plain<2>(a, st); break;
     case 3: launch_plain<3>(a, st); break;
     case 4: launch_plain<4>(a, st); break;

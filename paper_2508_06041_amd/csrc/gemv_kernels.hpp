@@ -7,6 +7,8 @@
 
 #include <cstdint>
 
+#include "layout_device.hpp"
+
 namespace dpllm {
 
 struct GemvArgs {
@@ -20,12 +22,6 @@ struct GemvArgs {
   uint16_t* y;               // fp16 [B][out]
   int out, in, ncw, nrq;
 };
-
-__device__ __forceinline__ float wave_sum_f32(float v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
-  return v;
-}
 
 // Plain kernel: one wave per row quad, one code bit at a time.  Serves every (k, B).
 template <int B>
@@ -50,7 +46,7 @@ __global__ void __launch_bounds__(256) gemv_plain_kernel(GemvArgs a) {
     for (int q = 0; q < 32; ++q) {
       uint32_t code[4] = {0, 0, 0, 0};
       for (int b = 0; b < k; ++b) {
-        int pos = (q - b) & 31;  // plane b keeps column q at bit q - b
+        int pos = (col_to_pos(q) - b) & 31;  // plane b keeps column q at bit pos(q) - b
         code[0] = (code[0] << 1) | ((w[b].x >> pos) & 1u);
         code[1] = (code[1] << 1) | ((w[b].y >> pos) & 1u);
         code[2] = (code[2] << 1) | ((w[b].z >> pos) & 1u);
@@ -72,7 +68,9 @@ __global__ void __launch_bounds__(256) gemv_plain_kernel(GemvArgs a) {
   for (int r = 0; r < 4; ++r)
 #pragma unroll
     for (int b = 0; b < B; ++b) {
-      float s = wave_sum_f32(acc[r][b]);
+      float s = acc[r][b];
+#pragma unroll
+      for (int sh = 32; sh >= 1; sh >>= 1) s += __shfl_xor(s, sh, 64);
       int o = rq * 4 + r;
       if (lane == 0 && o < a.out) a.y[(size_t)b * a.out + o] = __half_as_ushort(__float2half_rn(s));
     }
