@@ -123,7 +123,11 @@ int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* 
  * ys[id], batch 1, all on `stream` with no host synchronisation.  xs, ys: host arrays of
  * n_linears device pointers (fp16 [in_id], fp16 [out_id]).  k_dev, e_dev: device arrays
  * of n_linears entries receiving every linear's bitwidth and estimate.  Results equal
- * those of running the linears one after another.  Errors: EINVAL, ESTATE, EHIP. */
+ * those of running the linears one after another: consecutive linears that do not touch
+ * each other's inputs and outputs share launches, dependent ones are ordered on the stream.
+ * The first call, and any call after the pointers, selectors or thresholds changed,
+ * rebuilds the launch plan (it drains `stream` and copies two small tables); calls with an
+ * unchanged plan only enqueue kernels.  Errors: EINVAL, ESTATE, ESHAPE, EHIP. */
 int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev,
                       float* e_dev, void* stream);
 

@@ -1,7 +1,8 @@
 // Host side of the C boundary declared in include/dpllm.h: argument checks, the model object,
-// load-time re-tiling and kernel launches.  No kernel arithmetic lives here.
+// load-time re-tiling, launch planning and kernel launches.  No kernel arithmetic lives here.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -15,6 +16,7 @@
 #include "gemv_fast.hpp"
 #include "gemv_kernels.hpp"
 #include "layout.hpp"
+#include "selector_kernels.hpp"
 
 using namespace dpllm;
 
@@ -42,13 +44,47 @@ struct Linear {
   }
 };
 
+// A decode step is cut into phases: maximal runs of consecutive linears none of which reads or overwrites
+// what an earlier linear of the run writes.  Inside a phase all selectors run in one launch and all GEMVs
+// of one candidate pair in another; phases run one after the other on the stream, so the result equals
+// running the linears strictly in order.
+struct GemvLaunch {
+  int ka, kb;          // kernel instance; ka == kb == 0: the plain kernel, one launch per job
+  int first, count;    // slice of the device job table
+  int blocks;
+};
+struct Phase {
+  int sel_first, sel_count, sel_blocks;
+  std::vector<GemvLaunch> gemv;
+};
+struct StepPlan {
+  bool valid = false;
+  uint64_t version = 0;
+  std::vector<const void*> xs;
+  std::vector<void*> ys;
+  int32_t* k_dev = nullptr;
+  float* e_dev = nullptr;
+  std::vector<Phase> phases;
+  std::vector<GemvJob> gemv_jobs;   // host copies (also used for plain launches)
+  std::vector<int> gemv_ids;        // linear id of every gemv job
+};
+
 }  // namespace
 
 struct dpllm_model {
   std::vector<Linear> linears;
   std::string err;
-  double* sel_partial = nullptr;   // [DPLLM_MAX_RANK][max splits]
+  uint64_t version = 1;            // bumped by every call that changes what a plan depends on
+  // workspace of the single-linear estimate call
+  double* sel_partial = nullptr;   // [DPLLM_MAX_RANK][kMaxSelSplits]
   unsigned* sel_counter = nullptr;
+  // decode-step plan and its device tables
+  StepPlan plan;
+  SelJob* d_sel_jobs = nullptr;
+  GemvJob* d_gemv_jobs = nullptr;
+  double* d_step_partial = nullptr;
+  size_t step_partial_cap = 0;
+  unsigned* d_step_counters = nullptr;
   int device = 0;
 };
 
@@ -92,73 +128,234 @@ Linear* get_linear(dpllm_model* m, int id, int* rc) {
   return lin;
 }
 
-int launch_selector(dpllm_model* m, const Linear& lin, const Selector& s, const void* x, float* e_dev,
-                    int32_t* k_dev, hipStream_t st) {
-  if (s.kind == DPLLM_SEL_PROJ) {
-    int nsplit = (lin.L.in + kSelSplitCols - 1) / kSelSplitCols;
-    if (nsplit > kMaxSelSplits) return fail(m, DPLLM_ESHAPE, "in = %d too wide for the selector workspace", lin.L.in);
-    dim3 grid(nsplit, s.r);
-    hipLaunchKernelGGL(selector_proj_kernel, grid, dim3(kSelThreads), 0, st, s.G, (const uint16_t*)x, lin.L.in,
-                       s.r, nsplit, m->sel_partial, m->sel_counter, s.T, s.l, s.h, e_dev, k_dev);
-  } else if (s.kind == DPLLM_SEL_LINREG) {
-    hipLaunchKernelGGL(selector_linreg_kernel, dim3(1), dim3(256), 0, st, (const uint16_t*)x, lin.L.in, s.alpha,
-                       s.beta, s.T, s.l, s.h, e_dev, k_dev);
-  } else {
-    hipLaunchKernelGGL(selector_fixed_kernel, dim3(1), dim3(1), 0, st, s.l, e_dev, k_dev);
+// ---- selector ---------------------------------------------------------------------------------------------
+SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, double* partial, unsigned* counter,
+                    float* e_dev, int32_t* k_dev) {
+  SelJob j;
+  j.G = s.G;
+  j.x = (const uint16_t*)x;
+  j.partial = partial;
+  j.counter = counter;
+  j.e_out = e_dev;
+  j.k_out = k_dev;
+  j.T = s.T; j.alpha = s.alpha; j.beta = s.beta;
+  j.in = lin.L.in; j.r = s.r;
+  j.nsplit = (lin.L.in + kSelSplitCols - 1) / kSelSplitCols;
+  j.l = s.l; j.h = s.h; j.kind = s.kind;
+  j.nblocks = sel_job_blocks(s.kind, lin.L.in, s.r);
+  j.block_start = 0;
+  return j;
+}
+
+// ---- GEMV -------------------------------------------------------------------------------------------------
+// Kernel instances: a fixed bitwidth k (k, k) and the adjacent candidate pairs (k, k + 1), k >= 3.  Anything
+// else (k < 3, non-adjacent pairs, batch > 1) is served by the plain kernel.
+bool has_fast_kernel(int ka, int kb) { return ka >= 3 && kb <= 8 && (kb == ka || kb == ka + 1); }
+
+template <int KA, int KB>
+void launch_fast_t(const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
+  hipLaunchKernelGGL((gemv_kernel<KA, KB>), dim3(blocks), dim3(64), 0, st, d_jobs, njobs, one);
+}
+
+void launch_fast(int ka, int kb, const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
+#define DPLLM_CASE(A, B) case (A) * 16 + (B): launch_fast_t<A, B>(d_jobs, njobs, one, blocks, st); break;
+  switch (ka * 16 + kb) {
+    DPLLM_CASE(3, 3) DPLLM_CASE(4, 4) DPLLM_CASE(5, 5) DPLLM_CASE(6, 6) DPLLM_CASE(7, 7) DPLLM_CASE(8, 8)
+    DPLLM_CASE(3, 4) DPLLM_CASE(4, 5) DPLLM_CASE(5, 6) DPLLM_CASE(6, 7) DPLLM_CASE(7, 8)
+    default: break;
   }
-  HIP_TRY(m, hipGetLastError());
-  return DPLLM_OK;
+#undef DPLLM_CASE
+}
+
+GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y) {
+  GemvJob j;
+  j.arena = lin.arena;
+  j.x = (const uint16_t*)x;
+  j.y = (uint16_t*)y;
+  j.k_dev = k_dev;
+  j.plane_stride_u4 = (uint32_t)(lin.L.plane_bytes / 16);
+  j.lut_off_a = (uint32_t)lin.L.lut_offset[ka];
+  j.lut_off_b = (uint32_t)lin.L.lut_offset[kb];
+  j.ka = ka; j.kb = kb;
+  j.out = lin.L.out; j.ncw = lin.L.ncw; j.nrq = lin.L.nrq;
+  j.rq_per_block = 1;
+  j.block_start = 0;
+  return j;
+}
+
+// row quads one wavefront streams: enough wavefronts to fill the chip several times over, long enough runs
+// to amortise the pipeline fill
+int pick_rq_per_block(long total_rq) {
+  long r = total_rq / 8192;
+  return (int)std::min<long>(8, std::max<long>(1, r));
 }
 
 template <int B>
-void launch_plain(const GemvArgs& a, hipStream_t st) {
-  dim3 grid((a.nrq + 3) / 4);
-  hipLaunchKernelGGL(gemv_plain_kernel<B>, grid, dim3(256), 0, st, a);
+void launch_plain_t(const GemvArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(gemv_plain_kernel<B>, dim3((a.nrq + 3) / 4), dim3(256), 0, st, a);
 }
 
-int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y,
-                int B, hipStream_t st) {
+int launch_plain(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y,
+                 int B, hipStream_t st) {
   GemvArgs a;
   a.planes = lin.planes();
   a.plane_stride_u4 = lin.L.plane_bytes / 16;
-  a.ka = ka;
-  a.kb = kb;
+  a.ka = ka; a.kb = kb;
   a.lut_a = lin.lut(ka);
   a.lut_b = k_dev ? lin.lut(kb) : nullptr;
   a.k_dev = k_dev;
   a.x = (const uint16_t*)x;
   a.y = (uint16_t*)y;
-  a.out = lin.L.out;
-  a.in = lin.L.in;
-  a.ncw = lin.L.ncw;
-  a.nrq = lin.L.nrq;
+  a.out = lin.L.out; a.in = lin.L.in; a.ncw = lin.L.ncw; a.nrq = lin.L.nrq;
   switch (B) {
-    case 1: {
-      GemvJob j;
-      j.arena = lin.arena;
-      j.x = (const uint16_t*)x;
-      j.y = (uint16_t*)y;
-      j.k_dev = k_dev;
-      j.plane_stride_u4 = (uint32_t)(lin.L.plane_bytes / 16);
-      j.lut_off_a = (uint32_t)lin.L.lut_offset[ka];
-      j.lut_off_b = (uint32_t)lin.L.lut_offset[kb];
-      j.ka = ka; j.kb = kb;
-      j.out = lin.L.out; j.ncw = lin.L.ncw; j.nrq = lin.L.nrq;
-      j.block_start = 0;
-      hipLaunchKernelGGL(gemv_one_kernel, dim3(lin.L.nrq), dim3(64), 0, st, j);
-      break;
-    }
-    case 2: launch_plain<2>(a, st); break;
-    case 3: launch_plain<3>(a, st); break;
-    case 4: launch_plain<4>(a, st); break;
-    case 5: launch_plain<5>(a, st); break;
-    case 6: launch_plain<6>(a, st); break;
-    case 7: launch_plain<7>(a, st); break;
-    case 8: launch_plain<8>(a, st); break;
+    case 1: launch_plain_t<1>(a, st); break;
+    case 2: launch_plain_t<2>(a, st); break;
+    case 3: launch_plain_t<3>(a, st); break;
+    case 4: launch_plain_t<4>(a, st); break;
+    case 5: launch_plain_t<5>(a, st); break;
+    case 6: launch_plain_t<6>(a, st); break;
+    case 7: launch_plain_t<7>(a, st); break;
+    case 8: launch_plain_t<8>(a, st); break;
     default: return fail(m, DPLLM_ESHAPE, "batch %d outside [1, %d]", B, DPLLM_MAX_BATCH);
   }
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
+}
+
+int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y,
+                int B, hipStream_t st) {
+  if (B != 1 || !has_fast_kernel(ka, kb)) return launch_plain(m, lin, ka, kb, k_dev, x, y, B, st);
+  GemvJob j = make_gemv_job(lin, ka, kb, k_dev, x, y);
+  j.rq_per_block = pick_rq_per_block(lin.L.nrq);
+  int blocks = (lin.L.nrq + j.rq_per_block - 1) / j.rq_per_block;
+  launch_fast(ka, kb, nullptr, 1, j, blocks, st);
+  HIP_TRY(m, hipGetLastError());
+  return DPLLM_OK;
+}
+
+// ---- decode-step planning ------------------------------------------------------------------------------------
+bool overlap(const void* a, size_t an, const void* b, size_t bn) {
+  uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+  return a0 < b0 + bn && b0 < a0 + an;
+}
+
+int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev, float* e_dev,
+               hipStream_t st) {
+  const int n = (int)m->linears.size();
+  StepPlan& P = m->plan;
+  P.valid = false;
+  P.xs.assign(xs, xs + n);
+  P.ys.assign(ys, ys + n);
+  P.k_dev = k_dev;
+  P.e_dev = e_dev;
+  P.phases.clear();
+  P.gemv_jobs.clear();
+  P.gemv_ids.clear();
+  if (!m->d_sel_jobs) {
+    HIP_TRY(m, hipMalloc((void**)&m->d_sel_jobs, sizeof(SelJob) * n));
+    HIP_TRY(m, hipMalloc((void**)&m->d_gemv_jobs, sizeof(GemvJob) * n));
+    HIP_TRY(m, hipMalloc((void**)&m->d_step_counters, sizeof(unsigned) * n));
+    HIP_TRY(m, hipMemset(m->d_step_counters, 0, sizeof(unsigned) * n));
+  }
+  size_t need = 0;
+  for (int id = 0; id < n; ++id) {
+    const Selector& s = m->linears[id].sel[m->linears[id].active];
+    if (s.kind == DPLLM_SEL_PROJ) need += (size_t)s.r * ((m->linears[id].L.in + kSelSplitCols - 1) / kSelSplitCols);
+  }
+  if (need > m->step_partial_cap) {
+    if (m->d_step_partial) (void)hipFree(m->d_step_partial);
+    m->d_step_partial = nullptr;
+    m->step_partial_cap = 0;
+    HIP_TRY(m, hipMalloc((void**)&m->d_step_partial, sizeof(double) * need));
+    m->step_partial_cap = need;
+  }
+  std::vector<SelJob> sel_jobs;
+  size_t partial_off = 0;
+  int id = 0;
+  while (id < n) {
+    int end = id + 1;
+    for (; end < n; ++end) {  // extend the phase while linear `end` is independent of all of [id, end)
+      const Linear& le = m->linears[end];
+      bool dep = false;
+      for (int j = id; j < end && !dep; ++j) {
+        const Linear& lj = m->linears[j];
+        dep = overlap(xs[end], (size_t)le.L.in * 2, ys[j], (size_t)lj.L.out * 2) ||
+              overlap(ys[end], (size_t)le.L.out * 2, xs[j], (size_t)lj.L.in * 2) ||
+              overlap(ys[end], (size_t)le.L.out * 2, ys[j], (size_t)lj.L.out * 2);
+      }
+      if (dep) break;
+    }
+    Phase ph;
+    ph.sel_first = (int)sel_jobs.size();
+    ph.sel_count = end - id;
+    int sb = 0;
+    for (int j = id; j < end; ++j) {
+      const Linear& lin = m->linears[j];
+      const Selector& s = lin.sel[lin.active];
+      SelJob sj = make_sel_job(lin, s, xs[j], m->d_step_partial + partial_off, m->d_step_counters + j, e_dev + j,
+                               k_dev + j);
+      if (sj.nsplit > kMaxSelSplits) return fail(m, DPLLM_ESHAPE, "in = %d too wide for the selector", lin.L.in);
+      if (s.kind == DPLLM_SEL_PROJ) partial_off += (size_t)s.r * sj.nsplit;
+      sj.block_start = sb;
+      sb += sj.nblocks;
+      sel_jobs.push_back(sj);
+    }
+    ph.sel_blocks = sb;
+    // GEMV jobs of the phase, grouped by kernel instance in order of first appearance
+    std::vector<std::pair<int, int>> classes;
+    for (int j = id; j < end; ++j) {
+      const Selector& s = m->linears[j].sel[m->linears[j].active];
+      std::pair<int, int> c = has_fast_kernel(s.l, s.h) ? std::make_pair(s.l, s.h) : std::make_pair(0, 0);
+      if (std::find(classes.begin(), classes.end(), c) == classes.end()) classes.push_back(c);
+    }
+    for (auto c : classes) {
+      GemvLaunch gl;
+      gl.ka = c.first; gl.kb = c.second;
+      gl.first = (int)P.gemv_jobs.size();
+      long total_rq = 0;
+      for (int j = id; j < end; ++j) {
+        const Selector& s = m->linears[j].sel[m->linears[j].active];
+        bool fast = has_fast_kernel(s.l, s.h);
+        if ((fast && s.l == c.first && s.h == c.second) || (!fast && c.first == 0)) total_rq += m->linears[j].L.nrq;
+      }
+      const int rpb = pick_rq_per_block(total_rq);
+      int blocks = 0;
+      for (int j = id; j < end; ++j) {
+        const Linear& lin = m->linears[j];
+        const Selector& s = lin.sel[lin.active];
+        bool fast = has_fast_kernel(s.l, s.h);
+        if (!((fast && s.l == c.first && s.h == c.second) || (!fast && c.first == 0))) continue;
+        GemvJob gj = make_gemv_job(lin, s.l, s.h, s.l == s.h ? nullptr : k_dev + j, xs[j], ys[j]);
+        gj.rq_per_block = rpb;
+        gj.block_start = blocks;
+        blocks += (lin.L.nrq + rpb - 1) / rpb;
+        P.gemv_jobs.push_back(gj);
+        P.gemv_ids.push_back(j);
+      }
+      gl.count = (int)P.gemv_jobs.size() - gl.first;
+      gl.blocks = blocks;
+      ph.gemv.push_back(gl);
+    }
+    P.phases.push_back(ph);
+    id = end;
+  }
+  // The tables may still be read by a step enqueued earlier: drain the stream before replacing them.
+  HIP_TRY(m, hipStreamSynchronize(st));
+  HIP_TRY(m, hipMemcpy(m->d_sel_jobs, sel_jobs.data(), sizeof(SelJob) * sel_jobs.size(), hipMemcpyHostToDevice));
+  HIP_TRY(m, hipMemcpy(m->d_gemv_jobs, P.gemv_jobs.data(), sizeof(GemvJob) * P.gemv_jobs.size(),
+                       hipMemcpyHostToDevice));
+  P.version = m->version;
+  P.valid = true;
+  return DPLLM_OK;
+}
+
+void free_device(dpllm_model* m) {
+  if (m->sel_partial) (void)hipFree(m->sel_partial);
+  if (m->sel_counter) (void)hipFree(m->sel_counter);
+  if (m->d_sel_jobs) (void)hipFree(m->d_sel_jobs);
+  if (m->d_gemv_jobs) (void)hipFree(m->d_gemv_jobs);
+  if (m->d_step_partial) (void)hipFree(m->d_step_partial);
+  if (m->d_step_counters) (void)hipFree(m->d_step_counters);
 }
 
 }  // namespace
@@ -176,8 +373,7 @@ int dpllm_model_create(dpllm_model** out, int n_linears) {
       hipMalloc((void**)&m->sel_counter, 256) != hipSuccess ||
       hipMemset(m->sel_counter, 0, 256) != hipSuccess) {
     (void)hipGetLastError();
-    if (m->sel_partial) (void)hipFree(m->sel_partial);
-    if (m->sel_counter) (void)hipFree(m->sel_counter);
+    free_device(m);
     delete m;
     return DPLLM_EHIP;
   }
@@ -187,8 +383,7 @@ int dpllm_model_create(dpllm_model** out, int n_linears) {
 
 void dpllm_model_destroy(dpllm_model* m) {
   if (!m) return;
-  if (m->sel_partial) (void)hipFree(m->sel_partial);
-  if (m->sel_counter) (void)hipFree(m->sel_counter);
+  free_device(m);
   delete m;
 }
 
@@ -258,6 +453,7 @@ int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin, 
   lin.loaded = true;
   lin.L = L;
   lin.arena = (char*)dev_arena;
+  m->version++;
   return DPLLM_OK;
 }
 
@@ -288,6 +484,7 @@ int dpllm_set_selector(dpllm_model* m, int id, int l, int h, int kind, const voi
   s.set = true; s.l = l; s.h = h; s.kind = kind; s.r = r; s.G = (const uint16_t*)G_dev;
   s.alpha = alpha; s.beta = beta; s.T = T;
   lin->active = slot;
+  m->version++;
   return DPLLM_OK;
 }
 
@@ -299,6 +496,7 @@ int dpllm_set_threshold(dpllm_model* m, int id, int l, int h, float T) {
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
   lin->sel[slot].T = T;
+  m->version++;
   return DPLLM_OK;
 }
 
@@ -309,6 +507,7 @@ int dpllm_set_active_pair(dpllm_model* m, int id, int l, int h) {
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
   lin->active = slot;
+  m->version++;
   return DPLLM_OK;
 }
 
@@ -321,7 +520,12 @@ int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, floa
   if ((uintptr_t)x_dev % 16) return fail(m, DPLLM_EINVAL, "x not 16-byte aligned");
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
-  return launch_selector(m, *lin, lin->sel[slot], x_dev, e_dev, k_dev, (hipStream_t)stream);
+  SelJob j = make_sel_job(*lin, lin->sel[slot], x_dev, m->sel_partial, m->sel_counter, e_dev, k_dev);
+  if (j.nsplit > kMaxSelSplits) return fail(m, DPLLM_ESHAPE, "in = %d too wide for the selector", lin->L.in);
+  hipLaunchKernelGGL(selector_kernel, dim3(j.nblocks), dim3(kSelThreads), 0, (hipStream_t)stream,
+                     (const SelJob*)nullptr, 1, j);
+  HIP_TRY(m, hipGetLastError());
+  return DPLLM_OK;
 }
 
 int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* x_dev, void* y_dev, int B,
@@ -339,7 +543,7 @@ int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* 
   if (!k_dev) return fail(m, DPLLM_EINVAL, "k < 0 needs k_dev");
   if (lin->active < 0) return fail(m, DPLLM_ESTATE, "linear %d has no active pair", id);
   const Selector& s = lin->sel[lin->active];
-  return launch_gemv(m, *lin, s.l, s.h, k_dev, x_dev, y_dev, B, (hipStream_t)stream);
+  return launch_gemv(m, *lin, s.l, s.h, s.l == s.h ? nullptr : k_dev, x_dev, y_dev, B, (hipStream_t)stream);
 }
 
 int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev, float* e_dev,
@@ -347,22 +551,39 @@ int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, in
   if (!m) return DPLLM_EINVAL;
   if (!xs || !ys || !k_dev || !e_dev) return fail(m, DPLLM_EINVAL, "null pointer");
   const int n = (int)m->linears.size();
-  for (int id = 0; id < n; ++id) {
-    const Linear& lin = m->linears[id];
-    if (!lin.loaded) return fail(m, DPLLM_ESTATE, "linear %d is not loaded", id);
-    if (lin.active < 0) return fail(m, DPLLM_ESTATE, "linear %d has no selector", id);
-    if (!xs[id] || !ys[id]) return fail(m, DPLLM_EINVAL, "null x or y for linear %d", id);
-    if ((uintptr_t)xs[id] % 16) return fail(m, DPLLM_EINVAL, "x of linear %d not 16-byte aligned", id);
+  StepPlan& P = m->plan;
+  bool reuse = P.valid && P.version == m->version && P.k_dev == k_dev && P.e_dev == e_dev &&
+               std::equal(xs, xs + n, P.xs.begin()) && std::equal(ys, ys + n, P.ys.begin());
+  if (!reuse) {
+    for (int id = 0; id < n; ++id) {
+      const Linear& lin = m->linears[id];
+      if (!lin.loaded) return fail(m, DPLLM_ESTATE, "linear %d is not loaded", id);
+      if (lin.active < 0) return fail(m, DPLLM_ESTATE, "linear %d has no selector", id);
+      if (!xs[id] || !ys[id]) return fail(m, DPLLM_EINVAL, "null x or y for linear %d", id);
+      if ((uintptr_t)xs[id] % 16) return fail(m, DPLLM_EINVAL, "x of linear %d not 16-byte aligned", id);
+    }
+    int rc = build_plan(m, xs, ys, k_dev, e_dev, (hipStream_t)stream);
+    if (rc != DPLLM_OK) return rc;
   }
   hipStream_t st = (hipStream_t)stream;
-  for (int id = 0; id < n; ++id) {
-    const Linear& lin = m->linears[id];
-    const Selector& s = lin.sel[lin.active];
-    int rc = launch_selector(m, lin, s, xs[id], e_dev + id, k_dev + id, st);
-    if (rc != DPLLM_OK) return rc;
-    rc = launch_gemv(m, lin, s.l, s.h, k_dev + id, xs[id], ys[id], 1, st);
-    if (rc != DPLLM_OK) return rc;
+  SelJob none{};
+  GemvJob gnone{};
+  for (const Phase& ph : P.phases) {
+    hipLaunchKernelGGL(selector_kernel, dim3(ph.sel_blocks), dim3(kSelThreads), 0, st,
+                       (const SelJob*)(m->d_sel_jobs + ph.sel_first), ph.sel_count, none);
+    for (const GemvLaunch& gl : ph.gemv) {
+      if (gl.ka != 0) {
+        launch_fast(gl.ka, gl.kb, m->d_gemv_jobs + gl.first, gl.count, gnone, gl.blocks, st);
+      } else {
+        for (int i = gl.first; i < gl.first + gl.count; ++i) {
+          const GemvJob& j = P.gemv_jobs[i];
+          int rc = launch_plain(m, m->linears[P.gemv_ids[i]], j.ka, j.kb, j.k_dev, j.x, j.y, 1, st);
+          if (rc != DPLLM_OK) return rc;
+        }
+      }
+    }
   }
+  HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
 

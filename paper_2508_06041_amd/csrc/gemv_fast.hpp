@@ -1,9 +1,11 @@
 // Any-precision GEMV for gfx950, batch 1: y[o] = sum_c LUT_k[o][code_k(o,c)] * x[c]   (paper Sec. 3: the
 // linear operation of a decode step; Sec. 2.2: the k-bit model is the top k planes of the parent).
 //
-// Work split: one 64-lane wavefront (= one workgroup) owns one row quad and walks its columns in strips
-// of 64 words; a lane loads one 128-bit value per plane and strip (4 rows x 32 columns), so a wavefront
-// load is 1 KiB of contiguous memory per plane.  Only planes 0..k-1 are read.
+// Work split: one 64-lane wavefront (= one workgroup) owns a run of consecutive row quads and streams
+// them strip by strip (strip = 4 rows x 64 words of 32 columns).  A lane loads one 128-bit value per plane
+// and strip, so a wavefront load is 1 KiB of contiguous memory per plane; only planes 0..k-1 are read.  The
+// loads of strip t+1 (also across row-quad boundaries) are in flight while strip t is decoded, which keeps
+// HBM busy during the ALU-heavy decode.
 //
 // Decoding: the layout keeps the k bits of a weight at adjacent descending positions of planes 0..k-1
 // (see layout_device.hpp), so code fields are built by mask-merging whole plane words (v_bfi_b32), never
@@ -16,7 +18,7 @@
 //             per weight.
 // The per-row tables sit in LDS (wavefront-private: 64 B..2 KiB); activations are read from global memory
 // (L1/L2 hits) straight into packed registers, because LDS lookups are the scarcest resource at low k.
-// All accumulation is fp32; the four row sums are reduced across the wavefront at the end.
+// All accumulation is fp32; the four row sums are reduced across the wavefront with DPP adds.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -28,6 +30,7 @@ namespace dpllm {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct GemvJob {
   const char* arena;          // device planes start here; plane b at + b * plane_stride_u4 * 16 bytes
@@ -38,33 +41,61 @@ struct GemvJob {
   uint32_t lut_off_a, lut_off_b;  // byte offsets of the ka / kb tables inside the arena
   int32_t ka, kb;
   int32_t out, ncw, nrq;
+  int32_t rq_per_block;       // consecutive row quads one wavefront streams
   int32_t block_start;        // index of this job's first workgroup inside a multi-job grid
 };
 
 __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
 
-__device__ __forceinline__ float wave_sum_f32(float v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+  int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false);
+  return v + __builtin_bit_cast(float, moved);
+}
+
+// sum over the 64 lanes; the total is valid in lane 63
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+  v = dpp_add<0xB1, 0xf>(v);   // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E, 0xf>(v);   // quad_perm [2,3,0,1]
+  v = dpp_add<0x141, 0xf>(v);  // row_half_mirror
+  v = dpp_add<0x140, 0xf>(v);  // row_mirror: every lane of a 16-lane row holds the row sum
+  v = dpp_add<0x142, 0xa>(v);  // row_bcast15 into rows 1 and 3
+  v = dpp_add<0x143, 0xc>(v);  // row_bcast31 into rows 2 and 3
   return v;
 }
 
-__device__ __forceinline__ u32x4 load_stream(const u32x4* p) { return __builtin_nontemporal_load(p); }
+// Pointers read from a job record are generic; the kernels turn them into global-address-space pointers so
+// that loads use the vector-memory counter only and do not tie up the LDS counter the lookups wait on.
+#define DPLLM_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ const DPLLM_GLOBAL T* as_global(const T* p) { return (const DPLLM_GLOBAL T*)p; }
+template <class T>
+__device__ __forceinline__ DPLLM_GLOBAL T* as_global(T* p) { return (DPLLM_GLOBAL T*)p; }
 
-// ---- where the byte field of a column ends up after the merge tree (all compile-time) -------------------
+__device__ __forceinline__ u32x4 load_stream(const DPLLM_GLOBAL u32x4* p) { return __builtin_nontemporal_load(p); }
+
+// ---- per-bitwidth decode scheme (all compile-time) ----------------------------------------------------
+// kPair : k = 3, byte = 4 * (8 a + b), table of fp16 pairs, v_dot2_f32_f16
+// kF32  : k <= 5, byte = code << 2, table of fp32 values, v_fma_f32 (activations converted once per strip)
+// kF16  : k >= 6, byte = code << 1 (k = 8: code), table of fp16 values, v_fma_mix_f32
+enum class Scheme { kPair, kF32, kF16 };
 template <int K>
-struct ByteFieldMap {
-  static constexpr int d = (K == 8) ? 0 : 7 - K;  // plane b uses tree slot b + d; empty slots read as zero
-  __host__ __device__ static constexpr int top(int col) { return (col_to_pos(col) + d) & 31; }  // field top bit
+struct Decode {
+  static constexpr Scheme scheme = (K == 3) ? Scheme::kPair : (K <= 5 ? Scheme::kF32 : Scheme::kF16);
+  static constexpr int shift = (scheme == Scheme::kF32) ? 2 : 1;        // log2 of the table entry size
+  static constexpr int d = (K == 8) ? 0 : 8 - K - shift;                 // plane b uses merge-tree slot b + d
+  static constexpr int row_bytes = (K == 3) ? 256 : ((1 << K) << shift); // LDS bytes of one row's table
+  // byte field of column `col`: which of the eight merged words, and which byte after the alignment rotation
+  __host__ __device__ static constexpr int top(int col) { return (col_to_pos(col) + d) & 31; }
   __host__ __device__ static constexpr int word(int col) { return top(col) & 7; }
   __host__ __device__ static constexpr int rot(int c) { return (c + 1) & 7; }
   __host__ __device__ static constexpr int byte(int col) { return ((top(col) - rot(word(col))) & 31) >> 3; }
 };
 
-// planes of one row -> eight words, each four byte-aligned fields
+// planes of one row -> eight words, each four byte-aligned fields [code << shift]
 template <int K>
 __device__ __forceinline__ void merge_byte_fields(const uint32_t (&w)[K], uint32_t (&R)[8]) {
-  constexpr int d = ByteFieldMap<K>::d;
+  constexpr int d = Decode<K>::d;
   uint32_t v[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) v[s] = (s >= d && s < d + K) ? w[(s >= d && s < d + K) ? s - d : 0] : 0u;
@@ -92,156 +123,413 @@ __device__ __forceinline__ void merge_byte_fields(const uint32_t (&w)[K], uint32
   R[7] = bfi(field_mask(8, 7, 4), B[0][3], B[1][3]);
 }
 
-// one row x 32 columns, single lookups; tbl = this row's fp16 table in LDS
-template <int K, int COL>
-__device__ __forceinline__ _Float16 lookup_col(const uint32_t (&R)[8], const char* tbl) {
-  using M = ByteFieldMap<K>;
-  uint32_t f = (R[M::word(COL)] >> (8 * M::byte(COL))) & 0xffu;
-  if (K == 8) f <<= 1;
-  return *reinterpret_cast<const _Float16*>(tbl + f);
-}
-
-template <int K, int I>
-__device__ __forceinline__ float mac_pairs(const uint32_t (&R)[8], const uint32_t (&xp)[16], const char* tbl, float acc) {
-  if constexpr (I < 16) {
-    half2_t xv = __builtin_bit_cast(half2_t, xp[I]);
-    acc = __builtin_fmaf((float)lookup_col<K, 2 * I>(R, tbl), (float)xv.x, acc);
-    acc = __builtin_fmaf((float)lookup_col<K, 2 * I + 1>(R, tbl), (float)xv.y, acc);
-    return mac_pairs<K, I + 1>(R, xp, tbl, acc);
-  } else {
-    return acc;
+// k = 3: planes of one row -> four words of four bytes 4 * (8 a + b), columns (2i, 2i+1), i = 4 jj + n
+__device__ __forceinline__ void merge_pair_fields(const uint32_t (&w)[3], uint32_t (&T)[4]) {
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const uint32_t m0 = rotl_c(0x90909090u, 2 * jj), m1 = rotl_c(0x48484848u, 2 * jj), m2 = rotl_c(0x24242424u, 2 * jj);
+    uint32_t o = (w[0] & m0) | (w[1] & m1) | (w[2] & m2);
+    T[jj] = jj ? __builtin_rotateright32(o, 2 * jj) : o;
   }
 }
 
-template <int K>
-__device__ __forceinline__ float row_dot(const uint32_t (&w)[K], const uint32_t (&xp)[16], const char* tbl, float acc) {
-  if constexpr (K == 3) {
-    // pair lookups: byte n of merged word jj holds 4 * (8 a + b) for columns (2i, 2i+1), i = 4 jj + n
-    constexpr uint32_t m0 = 0x90909090u;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const int j = 2 * jj;
-      uint32_t o = (w[0] & rotl_c(m0, j)) | (w[1] & rotl_c(m0 >> 1, j)) | (w[2] & rotl_c(m0 >> 2, j));
-      uint32_t t = __builtin_rotateright32(o, j);
-#pragma unroll
-      for (int n = 0; n < 4; ++n) {
-        uint32_t f = (t >> (8 * n)) & 0xffu;
-        half2_t wv = __builtin_bit_cast(half2_t, *reinterpret_cast<const uint32_t*>(tbl + f));
-        acc = __builtin_amdgcn_fdot2(wv, __builtin_bit_cast(half2_t, xp[4 * jj + n]), acc, false);
-      }
-    }
-    return acc;
+// byte n of a word, scaled: two double-rate instructions at most
+template <int N, bool TIMES2 = false>
+__device__ __forceinline__ uint32_t byte_of(uint32_t w) {
+  if constexpr (TIMES2) {
+    if constexpr (N == 0) return (w << 1) & 0x1feu;
+    else return (w >> (8 * N - 1)) & 0x1feu;
   } else {
-    uint32_t R[8];
-    merge_byte_fields<K>(w, R);
-    return mac_pairs<K, 0>(R, xp, tbl, acc);
+    if constexpr (N == 0) return w & 0xffu;
+    else if constexpr (N == 3) return w >> 24;
+    else return (w >> (8 * N)) & 0xffu;
   }
 }
 
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+
 template <int K>
-struct Strip {
-  u32x4 w[K];
-  u32x4 x[4];
+struct PlaneStrip {
+  u32x4 w[K];   // 4 rows x 32 columns of planes 0..K-1
+};
+struct XStrip {
+  u32x4 x[4];   // the lane's 32 activations as 16 fp16 pairs
 };
 
+// Loads are never predicated: a lane past the end of a ragged strip re-reads the last word (its result is
+// discarded at compute time).  Unconditional issue keeps the compiler's outstanding-load counts exact, so
+// it waits only for the strip it is about to decode and leaves the prefetched ones in flight.
 template <int K>
-__device__ __forceinline__ void load_strip(Strip<K>& s, const GemvJob& job, int rq, int cw) {
-  if (cw < job.ncw) {
-    const u32x4* p = reinterpret_cast<const u32x4*>(job.arena) + (size_t)rq * job.ncw + cw;
+__device__ __forceinline__ void load_planes(PlaneStrip<K>& s, const GemvJob& job, int rq, int cw) {
+  const int cwc = min(cw, job.ncw - 1);
+  const DPLLM_GLOBAL u32x4* p = as_global(reinterpret_cast<const u32x4*>(job.arena)) + (size_t)rq * job.ncw + cwc;
 #pragma unroll
-    for (int b = 0; b < K; ++b) s.w[b] = load_stream(p + (size_t)b * job.plane_stride_u4);
-    const u32x4* xp = reinterpret_cast<const u32x4*>(job.x) + (size_t)cw * 4;
+  for (int b = 0; b < K; ++b) s.w[b] = load_stream(p + (size_t)b * job.plane_stride_u4);
+}
+
+__device__ __forceinline__ void load_x(XStrip& s, const GemvJob& job, int cw) {
+  const int cwc = min(cw, job.ncw - 1);
+  const DPLLM_GLOBAL u32x4* xp = as_global(reinterpret_cast<const u32x4*>(job.x)) + (size_t)cwc * 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) s.x[i] = xp[i];
+  for (int i = 0; i < 4; ++i) s.x[i] = xp[i];
+}
+
+// Orders the LDS table writes of a wavefront against its own lookups.  A workgroup is a single wavefront and
+// the LDS executes one wavefront's operations in issue order, so only the compiler has to be held back; no
+// counter wait is wanted here (a workgroup barrier would also drain the prefetched global loads).
+__device__ __forceinline__ void lds_order() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int K>
+__host__ __device__ constexpr int row_table_bytes() { return Decode<K>::row_bytes; }
+template <int KA, int KB>
+__host__ __device__ constexpr int lds_bytes() {
+  return 4 * (row_table_bytes<KA>() > row_table_bytes<KB>() ? row_table_bytes<KA>() : row_table_bytes<KB>());
+}
+
+// Lookups run as a software pipeline of chunks of 8: the LDS reads of chunk c+1 are issued before the
+// multiply-adds of chunk c, so LDS latency overlaps ALU work inside one wavefront.
+// Chunk (jj, r) of the byte-field schemes: columns 8 jj .. 8 jj + 7 of row r.
+template <int K, int JJ>
+__device__ __forceinline__ void issue_chunk(const uint32_t (&R)[8], const char* tbl, uint32_t (&v)[8]) {
+  using D = Decode<K>;
+#define DPLLM_LOOKUP(N)                                                                                   \
+  {                                                                                                       \
+    constexpr int ce = 8 * JJ + 2 * N, co = ce + 1;                                                       \
+    uint32_t fe = byte_of<D::byte(ce), K == 8>(R[D::word(ce)]), fo = byte_of<D::byte(co), K == 8>(R[D::word(co)]); \
+    if constexpr (D::scheme == Scheme::kF32) {                                                            \
+      v[2 * N] = *reinterpret_cast<const uint32_t*>(tbl + fe);                                            \
+      v[2 * N + 1] = *reinterpret_cast<const uint32_t*>(tbl + fo);                                        \
+    } else {                                                                                              \
+      v[2 * N] = *reinterpret_cast<const uint16_t*>(tbl + fe);                                            \
+      v[2 * N + 1] = *reinterpret_cast<const uint16_t*>(tbl + fo);                                        \
+    }                                                                                                     \
+  }
+  DPLLM_LOOKUP(0) DPLLM_LOOKUP(1) DPLLM_LOOKUP(2) DPLLM_LOOKUP(3)
+#undef DPLLM_LOOKUP
+}
+
+template <int K>
+__device__ __forceinline__ void consume_chunk(const uint32_t (&v)[8], const uint32_t (&xp4)[4], const float (&xf)[8],
+                                              float& acc0, float& acc1) {
+  using D = Decode<K>;
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    if constexpr (D::scheme == Scheme::kF32) {
+      acc0 = __builtin_fmaf(__builtin_bit_cast(float, v[2 * n]), xf[2 * n], acc0);
+      acc1 = __builtin_fmaf(__builtin_bit_cast(float, v[2 * n + 1]), xf[2 * n + 1], acc1);
+    } else {
+      half2_t xv = __builtin_bit_cast(half2_t, xp4[n]);
+      acc0 = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)v[2 * n]), (float)xv.x, acc0);
+      acc1 = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)v[2 * n + 1]), (float)xv.y, acc1);
+    }
+  }
+}
+
+template <int K, int C>
+__device__ __forceinline__ void byte_pipeline(const uint32_t (&R)[4][8], const uint32_t (&xp)[16], const char* lds,
+                                              uint32_t (&va)[8], uint32_t (&vb)[8], float (&xf)[8], float (&acc)[8]) {
+  // chunk C = 4 * jj + r uses buffer va; the next chunk is issued into vb first
+  if constexpr (C < 16) {
+    constexpr int jj = C / 4, r = C % 4;
+    if constexpr (C + 1 < 16) issue_chunk<K, (C + 1) / 4>(R[(C + 1) % 4], lds + ((C + 1) % 4) * Decode<K>::row_bytes, vb);
+    sched_fence();
+    if constexpr (Decode<K>::scheme == Scheme::kF32 && r == 0) {
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        half2_t xv = __builtin_bit_cast(half2_t, xp[4 * jj + n]);
+        xf[2 * n] = (float)xv.x;
+        xf[2 * n + 1] = (float)xv.y;
+      }
+    }
+    const uint32_t xp4[4] = {xp[4 * jj], xp[4 * jj + 1], xp[4 * jj + 2], xp[4 * jj + 3]};
+    consume_chunk<K>(va, xp4, xf, acc[2 * r], acc[2 * r + 1]);
+    sched_fence();
+    byte_pipeline<K, C + 1>(R, xp, lds, vb, va, xf, acc);
+  }
+}
+
+// k = 3 chunk C = 2 * jj + half: rows 2 half, 2 half + 1, four pair lookups each
+template <int C>
+__device__ __forceinline__ void issue_pair_chunk(const uint32_t (&T)[4][4], const char* lds, uint32_t (&v)[8]) {
+  constexpr int jj = C / 2, r0 = 2 * (C % 2);
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    const uint32_t t = T[r0 + rr][jj];
+    const char* tbl = lds + (r0 + rr) * 256;
+    v[4 * rr + 0] = *reinterpret_cast<const uint32_t*>(tbl + byte_of<0>(t));
+    v[4 * rr + 1] = *reinterpret_cast<const uint32_t*>(tbl + byte_of<1>(t));
+    v[4 * rr + 2] = *reinterpret_cast<const uint32_t*>(tbl + byte_of<2>(t));
+    v[4 * rr + 3] = *reinterpret_cast<const uint32_t*>(tbl + byte_of<3>(t));
+  }
+}
+
+template <int C>
+__device__ __forceinline__ void pair_pipeline(const uint32_t (&T)[4][4], const uint32_t (&xp)[16], const char* lds,
+                                              uint32_t (&va)[8], uint32_t (&vb)[8], float (&acc)[8]) {
+  if constexpr (C < 8) {
+    constexpr int jj = C / 2, r0 = 2 * (C % 2);
+    if constexpr (C + 1 < 8) issue_pair_chunk<C + 1>(T, lds, vb);
+    sched_fence();
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        float& a = acc[2 * (r0 + rr) + (n & 1)];
+        a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, va[4 * rr + n]), __builtin_bit_cast(half2_t, xp[4 * jj + n]), a, false);
+      }
+    sched_fence();
+    pair_pipeline<C + 1>(T, xp, lds, vb, va, acc);
   }
 }
 
 template <int K>
-__device__ __forceinline__ constexpr int row_table_bytes() { return K == 3 ? 256 : (2 << K); }
-
-template <int K>
-__device__ __forceinline__ void compute_strip(const Strip<K>& s, int cw, int ncw, const char* lds, float (&acc)[4]) {
+__device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStrip& xs, int cw, int ncw, const char* lds,
+                                              float (&acc)[8]) {
   if (cw >= ncw) return;
   uint32_t xp[16];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    xp[4 * i + 0] = s.x[i].x;
-    xp[4 * i + 1] = s.x[i].y;
-    xp[4 * i + 2] = s.x[i].z;
-    xp[4 * i + 3] = s.x[i].w;
+    xp[4 * i + 0] = xs.x[i].x;
+    xp[4 * i + 1] = xs.x[i].y;
+    xp[4 * i + 2] = xs.x[i].z;
+    xp[4 * i + 3] = xs.x[i].w;
   }
+  uint32_t va[8], vb[8];
+  if constexpr (K == 3) {
+    uint32_t T[4][4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    uint32_t w[K];
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t w[3] = {s.w[0][r], s.w[1][r], s.w[2][r]};
+      merge_pair_fields(w, T[r]);
+    }
+    issue_pair_chunk<0>(T, lds, va);
+    pair_pipeline<0>(T, xp, lds, va, vb, acc);
+  } else {
+    uint32_t R[4][8];
 #pragma unroll
-    for (int b = 0; b < K; ++b) w[b] = s.w[b][r];
-    acc[r] = row_dot<K>(w, xp, lds + r * row_table_bytes<K>(), acc[r]);
+    for (int r = 0; r < 4; ++r) {
+      uint32_t w[K];
+#pragma unroll
+      for (int b = 0; b < K; ++b) w[b] = s.w[b][r];
+      merge_byte_fields<K>(w, R[r]);
+    }
+    float xf[8];
+    issue_chunk<K, 0>(R[0], lds, va);
+    byte_pipeline<K, 0>(R, xp, lds, va, vb, xf, acc);
   }
 }
 
-// one wavefront, one row quad
+// The tables of one row quad, fetched one row quad ahead into registers and written to LDS at the boundary.
 template <int K>
-__device__ __forceinline__ void gemv_rowquad(const GemvJob& job, uint32_t lut_off, int rq, int lane, char* lds) {
-  const uint16_t* lut = reinterpret_cast<const uint16_t*>(job.arena + lut_off) + ((size_t)rq * 4 << K);
-  Strip<K> s0, s1;
-  load_strip<K>(s0, job, rq, lane);
+struct TableRegs {
+  // per lane: k = 3 one pair entry per row; fp32 tables one entry per register; fp16 tables two
+  static constexpr int kEntries = 4 << K;  // table entries of a row quad
+  static constexpr int kDwords = (K == 3) ? 4
+                               : (Decode<K>::scheme == Scheme::kF32 ? (kEntries + 63) / 64 : (kEntries / 2 + 63) / 64);
+  uint32_t v[kDwords];
+};
+
+template <int K>
+__device__ __forceinline__ void fetch_tables(TableRegs<K>& t, const DPLLM_GLOBAL uint16_t* lut_base, int rq, int lane) {
+  const DPLLM_GLOBAL uint16_t* lut = lut_base + ((size_t)rq * 4 << K);
   if constexpr (K == 3) {
     const int a = lane >> 3, b = lane & 7;
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      reinterpret_cast<uint32_t*>(lds)[r * 64 + lane] = (uint32_t)lut[r * 8 + a] | ((uint32_t)lut[r * 8 + b] << 16);
+    for (int r = 0; r < 4; ++r) t.v[r] = (uint32_t)lut[r * 8 + a] | ((uint32_t)lut[r * 8 + b] << 16);
+  } else if constexpr (Decode<K>::scheme == Scheme::kF32) {
+    constexpr int entries = TableRegs<K>::kEntries;
+#pragma unroll
+    for (int i = 0; i < TableRegs<K>::kDwords; ++i) {
+      int e = i * 64 + lane;
+      t.v[i] = (entries >= 64 || e < entries) ? (uint32_t)lut[e] : 0u;
+    }
   } else {
-    constexpr int dwords = (4 << K) / 2;
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(lut);
-    for (int e = lane; e < dwords; e += 64) reinterpret_cast<uint32_t*>(lds)[e] = src[e];
-  }
-  __syncthreads();
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  const int ncw = job.ncw;
-  for (int c0 = 0; c0 < ncw; c0 += 128) {
-    if (c0 + 64 < ncw) load_strip<K>(s1, job, rq, c0 + 64 + lane);
-    compute_strip<K>(s0, c0 + lane, ncw, lds, acc);
-    if (c0 + 64 < ncw) {
-      if (c0 + 128 < ncw) load_strip<K>(s0, job, rq, c0 + 128 + lane);
-      compute_strip<K>(s1, c0 + 64 + lane, ncw, lds, acc);
+    constexpr int dwords = TableRegs<K>::kEntries / 2;
+    const DPLLM_GLOBAL uint32_t* src = reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(lut);
+#pragma unroll
+    for (int i = 0; i < TableRegs<K>::kDwords; ++i) {
+      int e = i * 64 + lane;
+      t.v[i] = (dwords >= 64 || e < dwords) ? src[e] : 0u;
     }
   }
+}
+
+template <int K>
+__device__ __forceinline__ void store_tables(const TableRegs<K>& t, char* lds, int lane) {
+  uint32_t* dst = reinterpret_cast<uint32_t*>(lds);
+  if constexpr (K == 3) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) dst[r * 64 + lane] = t.v[r];
+  } else if constexpr (Decode<K>::scheme == Scheme::kF32) {
+    constexpr int entries = TableRegs<K>::kEntries;
+#pragma unroll
+    for (int i = 0; i < TableRegs<K>::kDwords; ++i) {
+      int e = i * 64 + lane;
+      float f = (float)__builtin_bit_cast(_Float16, (uint16_t)t.v[i]);
+      if (entries >= 64 || e < entries) dst[e] = __builtin_bit_cast(uint32_t, f);
+    }
+  } else {
+    constexpr int dwords = TableRegs<K>::kEntries / 2;
+#pragma unroll
+    for (int i = 0; i < TableRegs<K>::kDwords; ++i) {
+      int e = i * 64 + lane;
+      if (dwords >= 64 || e < dwords) dst[e] = t.v[i];
+    }
+  }
+}
+
+__device__ __forceinline__ void finish_rowquad(const GemvJob& job, int rq, int lane, float (&acc)[8]) {
+  float s[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    float s = wave_sum_f32(acc[r]);
-    int o = rq * 4 + r;
-    if (lane == 0 && o < job.out) job.y[o] = __builtin_bit_cast(uint16_t, (_Float16)s);
+    s[r] = wave_sum_to_lane63(acc[2 * r] + acc[2 * r + 1]);
+    acc[2 * r] = acc[2 * r + 1] = 0.f;
+  }
+  if (lane == 63) {
+    half2_t lo = {(_Float16)s[0], (_Float16)s[1]}, hi = {(_Float16)s[2], (_Float16)s[3]};
+    DPLLM_GLOBAL uint16_t* y = as_global(job.y) + (size_t)rq * 4;
+    if (rq * 4 + 4 <= job.out && (reinterpret_cast<uintptr_t>(job.y) & 7) == 0) {
+      u32x2 v = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+      *reinterpret_cast<DPLLM_GLOBAL u32x2*>(y) = v;
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (rq * 4 + r < job.out) y[r] = __builtin_bit_cast(uint16_t, (_Float16)s[r]);
+    }
   }
 }
 
-__device__ __forceinline__ void gemv_dispatch(const GemvJob& job, int rq, int lane, char* lds) {
-  int k = job.ka;
-  uint32_t off = job.lut_off_a;
-  if (job.k_dev != nullptr) {
-    int kd = __builtin_amdgcn_readfirstlane(*job.k_dev);
-    if (kd == job.kb) { k = job.kb; off = job.lut_off_b; }
+// One wavefront streams row quads [rq0, rq1) of a job.  Plane strips travel through a ring of D register
+// buffers: the loads of strips t+1 .. t+D-1 are in flight while strip t is decoded (HBM latency under load
+// is several microseconds, so about 100 KiB per compute unit must be in flight to keep the memory busy).
+// XS = true (exactly two strips per row): the activations of both strips stay in registers for the whole
+// run.  XS = false: activations ride in a ring of their own, fetched with the planes (L2 hits).
+template <int K, int D, bool XS>
+struct StreamState {
+  PlaneStrip<K> pb[D];
+  XStrip xb[XS ? 2 : D];
+  TableRegs<K> tr;
+  float acc[8];
+  int rq0;
+  int lrq, lc0, lt;   // load cursor: row quad, first word of the strip, strip counter
+  int crq, cc0, ct;   // compute cursor
+  int total;
+};
+
+template <int K, int D, bool XS, int I>
+__device__ __forceinline__ bool stream_step(StreamState<K, D, XS>& st, const GemvJob& job,
+                                            const DPLLM_GLOBAL uint16_t* lut_base, int rq1, int lane, char* lds) {
+  const int ncw = job.ncw;
+  constexpr int slot = (I + D - 1) % D;
+  {
+    // past the end of the run the slot is refilled from the run's first strip (an L2 hit, never decoded)
+    const bool more = st.lt < st.total;
+    const int lrq = more ? st.lrq : st.rq0, lc0 = more ? st.lc0 : 0;
+    load_planes<K>(st.pb[slot], job, lrq, lc0 + lane);
+    if constexpr (!XS) load_x(st.xb[slot], job, lc0 + lane);
+    if (more) {
+      st.lt++;
+      st.lc0 += 64;
+      if (st.lc0 >= ncw) { st.lc0 = 0; st.lrq++; }
+    }
   }
-  switch (k) {
-    case 1: gemv_rowquad<1>(job, off, rq, lane, lds); break;
-    case 2: gemv_rowquad<2>(job, off, rq, lane, lds); break;
-    case 3: gemv_rowquad<3>(job, off, rq, lane, lds); break;
-    case 4: gemv_rowquad<4>(job, off, rq, lane, lds); break;
-    case 5: gemv_rowquad<5>(job, off, rq, lane, lds); break;
-    case 6: gemv_rowquad<6>(job, off, rq, lane, lds); break;
-    case 7: gemv_rowquad<7>(job, off, rq, lane, lds); break;
-    case 8: gemv_rowquad<8>(job, off, rq, lane, lds); break;
-    default: break;
+  compute_strip<K>(st.pb[I], st.xb[XS ? (I & 1) : I], st.cc0 + lane, ncw, lds, st.acc);
+  st.cc0 += 64;
+  if (st.cc0 >= ncw) {
+    finish_rowquad(job, st.crq, lane, st.acc);
+    st.cc0 = 0;
+    st.crq++;
+    if (st.crq < rq1) {
+      lds_order();
+      store_tables<K>(st.tr, lds, lane);
+      fetch_tables<K>(st.tr, lut_base, min(st.crq + 1, rq1 - 1), lane);
+      lds_order();
+    }
+  }
+  return ++st.ct == st.total;
+}
+
+template <int K, int D, bool XS, int I>
+__device__ __forceinline__ bool stream_round(StreamState<K, D, XS>& st, const GemvJob& job,
+                                             const DPLLM_GLOBAL uint16_t* lut_base, int rq1, int lane, char* lds) {
+  if constexpr (I < D) {
+    if (stream_step<K, D, XS, I>(st, job, lut_base, rq1, lane, lds)) return true;
+    return stream_round<K, D, XS, I + 1>(st, job, lut_base, rq1, lane, lds);
+  } else {
+    return false;
   }
 }
 
-__global__ void __launch_bounds__(64) gemv_one_kernel(GemvJob job) {
-  __shared__ __attribute__((aligned(16))) char lds[2048];
-  gemv_dispatch(job, blockIdx.x, threadIdx.x, lds);
+template <int K, int D, bool XS>
+__device__ __forceinline__ void gemv_stream(const GemvJob& job, uint32_t lut_off, int rq0, int rq1, int lane, char* lds) {
+  const DPLLM_GLOBAL uint16_t* lut_base = as_global(reinterpret_cast<const uint16_t*>(job.arena + lut_off));
+  const int ncw = job.ncw;
+  StreamState<K, D, XS> st;
+  const int ns = (ncw + 63) >> 6;
+  st.total = (rq1 - rq0) * ns;
+  st.rq0 = rq0;
+  st.lrq = rq0; st.lc0 = 0; st.lt = 0;
+  st.crq = rq0; st.cc0 = 0; st.ct = 0;
+#pragma unroll
+  for (int i = 0; i < D - 1; ++i) {
+    const bool more = st.lt < st.total;
+    const int lrq = more ? st.lrq : rq0, lc0 = more ? st.lc0 : 0;
+    load_planes<K>(st.pb[i], job, lrq, lc0 + lane);
+    if constexpr (!XS) load_x(st.xb[i], job, lc0 + lane);
+    if (more) {
+      st.lt++;
+      st.lc0 += 64;
+      if (st.lc0 >= ncw) { st.lc0 = 0; st.lrq++; }
+    }
+  }
+  if constexpr (XS) {
+    load_x(st.xb[0], job, lane);
+    load_x(st.xb[1], job, 64 + lane);
+  }
+  fetch_tables<K>(st.tr, lut_base, rq0, lane);
+  store_tables<K>(st.tr, lds, lane);
+  fetch_tables<K>(st.tr, lut_base, min(rq0 + 1, rq1 - 1), lane);
+  lds_order();
+#pragma unroll
+  for (int r = 0; r < 8; ++r) st.acc[r] = 0.f;
+  while (!stream_round<K, D, XS, 0>(st, job, lut_base, rq1, lane, lds)) {
+  }
 }
 
-// jobs[j].block_start ascending; block b belongs to the last job whose block_start <= b
-__global__ void __launch_bounds__(64) gemv_multi_kernel(const GemvJob* __restrict__ jobs, int njobs) {
-  __shared__ __attribute__((aligned(16))) char lds[2048];
+template <int K>
+__device__ __forceinline__ void gemv_stream_any(const GemvJob& job, uint32_t lut_off, int rq0, int rq1, int lane, char* lds) {
+  if (job.ncw > 64 && job.ncw <= 128)
+    gemv_stream<K, 4, true>(job, lut_off, rq0, rq1, lane, lds);
+  else
+    gemv_stream<K, 3, false>(job, lut_off, rq0, rq1, lane, lds);
+}
+
+template <int KA, int KB>
+__device__ __forceinline__ void gemv_block(const GemvJob& job, int block, int lane, char* lds) {
+  const int rq0 = block * job.rq_per_block;
+  const int rq1 = min(job.nrq, rq0 + job.rq_per_block);
+  if (rq0 >= rq1) return;
+  if constexpr (KA != KB) {
+    if (job.k_dev != nullptr && __builtin_amdgcn_readfirstlane(*as_global(job.k_dev)) == KB) {
+      gemv_stream_any<KB>(job, job.lut_off_b, rq0, rq1, lane, lds);
+      return;
+    }
+  }
+  gemv_stream_any<KA>(job, job.lut_off_a, rq0, rq1, lane, lds);
+}
+
+// jobs == nullptr: the single job passed by value; else block b belongs to the last job with block_start <= b
+template <int KA, int KB>
+__global__ void __launch_bounds__(64) gemv_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
+  __shared__ __attribute__((aligned(16))) char lds[lds_bytes<KA, KB>()];
+  if (jobs == nullptr) {
+    gemv_block<KA, KB>(one, blockIdx.x, threadIdx.x, lds);
+    return;
+  }
   const int b = blockIdx.x;
   int lo = 0, hi = njobs - 1;
   while (lo < hi) {
@@ -249,7 +537,7 @@ __global__ void __launch_bounds__(64) gemv_multi_kernel(const GemvJob* __restric
     if (jobs[mid].block_start <= b) lo = mid; else hi = mid - 1;
   }
   GemvJob job = jobs[lo];
-  gemv_dispatch(job, b - job.block_start, threadIdx.x, lds);
+  gemv_block<KA, KB>(job, b - job.block_start, threadIdx.x, lds);
 }
 
 }  // namespace dpllm
