@@ -49,7 +49,7 @@ extern "C" {
 
 #define DPLLM_MAX_BITS 8
 #define DPLLM_MAX_BATCH 8
-#define DPLLM_MAX_PAIRS 4   /* (l,h) candidate pairs kept per linear                    */
+#define DPLLM_MAX_PAIRS 8   /* (l,h) candidate pairs kept per linear                    */
 #define DPLLM_MAX_RANK 1024 /* projection rank r                                        */
 
 #define DPLLM_SEL_NONE 0   /* no estimator: always l                                     */
@@ -130,6 +130,16 @@ int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* 
  * unchanged plan only enqueue kernels.  Errors: EINVAL, ESTATE, ESHAPE, EHIP. */
 int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev,
                       float* e_dev, void* stream);
+
+/* The two halves of dpllm_decode_step, for callers that schedule them apart (Sec. 5.2:
+ * selectors fed by an earlier activation can run ahead of the GEMVs they steer) or time
+ * them apart.  parts = DPLLM_STEP_SELECT: every selector writes k_dev / e_dev.  parts =
+ * DPLLM_STEP_GEMV: every GEMV runs at the bitwidth k_dev already holds (l or h of the
+ * linear's active pair).  Both bits = dpllm_decode_step.  Same arguments, plan and errors. */
+#define DPLLM_STEP_SELECT 1
+#define DPLLM_STEP_GEMV 2
+int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev,
+                            float* e_dev, int parts, void* stream);
 
 /* Parity aid: writes the canonical k-bit codes of linear `id`, uint8 [out][in], read back
  * from the private device layout, to idx_dev (device).  Errors: EINVAL, ERANGE, ESTATE, EHIP. */

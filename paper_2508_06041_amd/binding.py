@@ -14,10 +14,11 @@ _LIB_PATH = os.path.join(_HERE, "libdpllm.so")
 DPLLM_OK, DPLLM_EINVAL, DPLLM_ESHAPE, DPLLM_ERANGE, DPLLM_ESTATE, DPLLM_EHIP = 0, -1, -2, -3, -4, -5
 DPLLM_SEL_NONE, DPLLM_SEL_PROJ, DPLLM_SEL_LINREG = 0, 1, 2
 DPLLM_MAX_BATCH = 8
+DPLLM_STEP_SELECT, DPLLM_STEP_GEMV = 1, 2
 
 SYMBOLS = ["dpllm_model_create", "dpllm_model_destroy", "dpllm_last_error", "dpllm_linear_device_bytes",
            "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair",
-           "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_debug_unpack"]
+           "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack"]
 
 
 class DpllmError(RuntimeError):
@@ -45,6 +46,7 @@ def _load():
     L.dpllm_estimate.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
     L.dpllm_gemv.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp]
     L.dpllm_decode_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
+    L.dpllm_decode_step_parts.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, i32, vp]
     L.dpllm_debug_unpack.argtypes = [vp, i32, i32, vp, vp]
     return L
 
@@ -154,6 +156,11 @@ class Model:
         xa = (C.c_void_p * self.n)(*[t.data_ptr() for t in xs])
         ya = (C.c_void_p * self.n)(*[t.data_ptr() for t in ys])
         _check(self.h, lib.dpllm_decode_step(self.h, xa, ya, _ptr(k_out), _ptr(e_out), _stream()))
+
+    def dpllm_decode_step_parts(self, xs, ys, k_out, e_out, parts):
+        xa = (C.c_void_p * self.n)(*[t.data_ptr() for t in xs])
+        ya = (C.c_void_p * self.n)(*[t.data_ptr() for t in ys])
+        _check(self.h, lib.dpllm_decode_step_parts(self.h, xa, ya, _ptr(k_out), _ptr(e_out), parts, _stream()))
 
     def dpllm_debug_unpack(self, id, k):
         out, in_, _, _ = self.shapes.get(id, (1, 32, 0, 0))

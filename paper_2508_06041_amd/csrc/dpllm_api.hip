@@ -546,9 +546,10 @@ int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* 
   return launch_gemv(m, *lin, s.l, s.h, s.l == s.h ? nullptr : k_dev, x_dev, y_dev, B, (hipStream_t)stream);
 }
 
-int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev, float* e_dev,
-                      void* stream) {
+int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev, float* e_dev,
+                            int parts, void* stream) {
   if (!m) return DPLLM_EINVAL;
+  if (parts < 1 || parts > (DPLLM_STEP_SELECT | DPLLM_STEP_GEMV)) return fail(m, DPLLM_EINVAL, "bad parts %d", parts);
   if (!xs || !ys || !k_dev || !e_dev) return fail(m, DPLLM_EINVAL, "null pointer");
   const int n = (int)m->linears.size();
   StepPlan& P = m->plan;
@@ -569,8 +570,10 @@ int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, in
   SelJob none{};
   GemvJob gnone{};
   for (const Phase& ph : P.phases) {
-    hipLaunchKernelGGL(selector_kernel, dim3(ph.sel_blocks), dim3(kSelThreads), 0, st,
-                       (const SelJob*)(m->d_sel_jobs + ph.sel_first), ph.sel_count, none);
+    if (parts & DPLLM_STEP_SELECT)
+      hipLaunchKernelGGL(selector_kernel, dim3(ph.sel_blocks), dim3(kSelThreads), 0, st,
+                         (const SelJob*)(m->d_sel_jobs + ph.sel_first), ph.sel_count, none);
+    if (!(parts & DPLLM_STEP_GEMV)) continue;
     for (const GemvLaunch& gl : ph.gemv) {
       if (gl.ka != 0) {
         launch_fast(gl.ka, gl.kb, m->d_gemv_jobs + gl.first, gl.count, gnone, gl.blocks, st);
@@ -585,6 +588,11 @@ int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, in
   }
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
+}
+
+int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev, float* e_dev,
+                      void* stream) {
+  return dpllm_decode_step_parts(m, xs, ys, k_dev, e_dev, DPLLM_STEP_SELECT | DPLLM_STEP_GEMV, stream);
 }
 
 int dpllm_debug_unpack(dpllm_model* m, int id, int k, uint8_t* idx_dev, void* stream) {
