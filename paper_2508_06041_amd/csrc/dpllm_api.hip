@@ -75,22 +75,14 @@ struct dpllm_model {
   std::vector<Linear> linears;
   std::string err;
   uint64_t version = 1;            // bumped by every call that changes what a plan depends on
-  // workspace of the single-linear estimate call
-  double* sel_partial = nullptr;   // [DPLLM_MAX_RANK][kMaxSelSplits]
-  unsigned* sel_counter = nullptr;
   // decode-step plan and its device tables
   StepPlan plan;
   SelJob* d_sel_jobs = nullptr;
   GemvJob* d_gemv_jobs = nullptr;
-  double* d_step_partial = nullptr;
-  size_t step_partial_cap = 0;
-  unsigned* d_step_counters = nullptr;
   int device = 0;
 };
 
 namespace {
-
-constexpr int kMaxSelSplits = 64;  // up to 65536 input columns
 
 int fail(dpllm_model* m, int code, const char* fmt, ...) {
   if (m) {
@@ -129,21 +121,15 @@ Linear* get_linear(dpllm_model* m, int id, int* rc) {
 }
 
 // ---- selector ---------------------------------------------------------------------------------------------
-SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, double* partial, unsigned* counter,
-                    float* e_dev, int32_t* k_dev) {
+SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* e_dev, int32_t* k_dev) {
   SelJob j;
   j.G = s.G;
   j.x = (const uint16_t*)x;
-  j.partial = partial;
-  j.counter = counter;
   j.e_out = e_dev;
   j.k_out = k_dev;
   j.T = s.T; j.alpha = s.alpha; j.beta = s.beta;
   j.in = lin.L.in; j.r = s.r;
-  j.nsplit = (lin.L.in + kSelSplitCols - 1) / kSelSplitCols;
   j.l = s.l; j.h = s.h; j.kind = s.kind;
-  j.nblocks = sel_job_blocks(s.kind, lin.L.in, s.r);
-  j.block_start = 0;
   return j;
 }
 
@@ -178,13 +164,13 @@ GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, c
   j.lut_off_b = (uint32_t)lin.L.lut_offset[kb];
   j.ka = ka; j.kb = kb;
   j.out = lin.L.out; j.ncw = lin.L.ncw; j.nrq = lin.L.nrq;
-  j.rq_per_block = 1;
+  j.nblocks = lin.L.nrq;
   j.block_start = 0;
   return j;
 }
 
-// row quads one wavefront streams: enough wavefronts to fill the chip several times over, long enough runs
-// to amortise the pipeline fill
+// row quads one wavefront streams (workgroup b of a job takes row quads b, b + nblocks, ...): enough
+// wavefronts to fill the chip several times over, long enough runs to amortise the pipeline fill
 int pick_rq_per_block(long total_rq) {
   long r = total_rq / 8192;
   return (int)std::min<long>(8, std::max<long>(1, r));
@@ -226,9 +212,9 @@ int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t
                 int B, hipStream_t st) {
   if (B != 1 || !has_fast_kernel(ka, kb)) return launch_plain(m, lin, ka, kb, k_dev, x, y, B, st);
   GemvJob j = make_gemv_job(lin, ka, kb, k_dev, x, y);
-  j.rq_per_block = pick_rq_per_block(lin.L.nrq);
-  int blocks = (lin.L.nrq + j.rq_per_block - 1) / j.rq_per_block;
-  launch_fast(ka, kb, nullptr, 1, j, blocks, st);
+  const int rpb = pick_rq_per_block(lin.L.nrq);
+  j.nblocks = (lin.L.nrq + rpb - 1) / rpb;
+  launch_fast(ka, kb, nullptr, 1, j, j.nblocks, st);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -254,23 +240,8 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   if (!m->d_sel_jobs) {
     HIP_TRY(m, hipMalloc((void**)&m->d_sel_jobs, sizeof(SelJob) * n));
     HIP_TRY(m, hipMalloc((void**)&m->d_gemv_jobs, sizeof(GemvJob) * n));
-    HIP_TRY(m, hipMalloc((void**)&m->d_step_counters, sizeof(unsigned) * n));
-    HIP_TRY(m, hipMemset(m->d_step_counters, 0, sizeof(unsigned) * n));
-  }
-  size_t need = 0;
-  for (int id = 0; id < n; ++id) {
-    const Selector& s = m->linears[id].sel[m->linears[id].active];
-    if (s.kind == DPLLM_SEL_PROJ) need += (size_t)s.r * ((m->linears[id].L.in + kSelSplitCols - 1) / kSelSplitCols);
-  }
-  if (need > m->step_partial_cap) {
-    if (m->d_step_partial) (void)hipFree(m->d_step_partial);
-    m->d_step_partial = nullptr;
-    m->step_partial_cap = 0;
-    HIP_TRY(m, hipMalloc((void**)&m->d_step_partial, sizeof(double) * need));
-    m->step_partial_cap = need;
   }
   std::vector<SelJob> sel_jobs;
-  size_t partial_off = 0;
   int id = 0;
   while (id < n) {
     int end = id + 1;
@@ -292,13 +263,8 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     for (int j = id; j < end; ++j) {
       const Linear& lin = m->linears[j];
       const Selector& s = lin.sel[lin.active];
-      SelJob sj = make_sel_job(lin, s, xs[j], m->d_step_partial + partial_off, m->d_step_counters + j, e_dev + j,
-                               k_dev + j);
-      if (sj.nsplit > kMaxSelSplits) return fail(m, DPLLM_ESHAPE, "in = %d too wide for the selector", lin.L.in);
-      if (s.kind == DPLLM_SEL_PROJ) partial_off += (size_t)s.r * sj.nsplit;
-      sj.block_start = sb;
-      sb += sj.nblocks;
-      sel_jobs.push_back(sj);
+      sel_jobs.push_back(make_sel_job(lin, s, xs[j], e_dev + j, k_dev + j));
+      sb += 1;
     }
     ph.sel_blocks = sb;
     // GEMV jobs of the phase, grouped by kernel instance in order of first appearance
@@ -326,9 +292,9 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
         bool fast = has_fast_kernel(s.l, s.h);
         if (!((fast && s.l == c.first && s.h == c.second) || (!fast && c.first == 0))) continue;
         GemvJob gj = make_gemv_job(lin, s.l, s.h, s.l == s.h ? nullptr : k_dev + j, xs[j], ys[j]);
-        gj.rq_per_block = rpb;
+        gj.nblocks = (lin.L.nrq + rpb - 1) / rpb;
         gj.block_start = blocks;
-        blocks += (lin.L.nrq + rpb - 1) / rpb;
+        blocks += gj.nblocks;
         P.gemv_jobs.push_back(gj);
         P.gemv_ids.push_back(j);
       }
@@ -350,12 +316,8 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
 }
 
 void free_device(dpllm_model* m) {
-  if (m->sel_partial) (void)hipFree(m->sel_partial);
-  if (m->sel_counter) (void)hipFree(m->sel_counter);
   if (m->d_sel_jobs) (void)hipFree(m->d_sel_jobs);
   if (m->d_gemv_jobs) (void)hipFree(m->d_gemv_jobs);
-  if (m->d_step_partial) (void)hipFree(m->d_step_partial);
-  if (m->d_step_counters) (void)hipFree(m->d_step_counters);
 }
 
 }  // namespace
@@ -368,10 +330,7 @@ int dpllm_model_create(dpllm_model** out, int n_linears) {
   dpllm_model* m = new (std::nothrow) dpllm_model();
   if (!m) return DPLLM_EINVAL;
   m->linears.resize(n_linears);
-  if (hipGetDevice(&m->device) != hipSuccess ||
-      hipMalloc((void**)&m->sel_partial, sizeof(double) * DPLLM_MAX_RANK * kMaxSelSplits) != hipSuccess ||
-      hipMalloc((void**)&m->sel_counter, 256) != hipSuccess ||
-      hipMemset(m->sel_counter, 0, 256) != hipSuccess) {
+  if (hipGetDevice(&m->device) != hipSuccess) {
     (void)hipGetLastError();
     free_device(m);
     delete m;
@@ -520,10 +479,8 @@ int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, floa
   if ((uintptr_t)x_dev % 16) return fail(m, DPLLM_EINVAL, "x not 16-byte aligned");
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
-  SelJob j = make_sel_job(*lin, lin->sel[slot], x_dev, m->sel_partial, m->sel_counter, e_dev, k_dev);
-  if (j.nsplit > kMaxSelSplits) return fail(m, DPLLM_ESHAPE, "in = %d too wide for the selector", lin->L.in);
-  hipLaunchKernelGGL(selector_kernel, dim3(j.nblocks), dim3(kSelThreads), 0, (hipStream_t)stream,
-                     (const SelJob*)nullptr, 1, j);
+  SelJob j = make_sel_job(*lin, lin->sel[slot], x_dev, e_dev, k_dev);
+  hipLaunchKernelGGL(selector_kernel, dim3(1), dim3(kSelThreads), 0, (hipStream_t)stream, (const SelJob*)nullptr, j);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -572,7 +529,7 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
   for (const Phase& ph : P.phases) {
     if (parts & DPLLM_STEP_SELECT)
       hipLaunchKernelGGL(selector_kernel, dim3(ph.sel_blocks), dim3(kSelThreads), 0, st,
-                         (const SelJob*)(m->d_sel_jobs + ph.sel_first), ph.sel_count, none);
+                         (const SelJob*)(m->d_sel_jobs + ph.sel_first), none);
     if (!(parts & DPLLM_STEP_GEMV)) continue;
     for (const GemvLaunch& gl : ph.gemv) {
       if (gl.ka != 0) {

@@ -41,7 +41,7 @@ struct GemvJob {
   uint32_t lut_off_a, lut_off_b;  // byte offsets of the ka / kb tables inside the arena
   int32_t ka, kb;
   int32_t out, ncw, nrq;
-  int32_t rq_per_block;       // consecutive row quads one wavefront streams
+  int32_t nblocks;            // workgroups of this job; workgroup b streams row quads b, b + nblocks, ...
   int32_t block_start;        // index of this job's first workgroup inside a multi-job grid
 };
 
@@ -133,7 +133,8 @@ __device__ __forceinline__ void merge_pair_fields(const uint32_t (&w)[3], uint32
   }
 }
 
-// byte n of a word, scaled: two double-rate instructions at most
+// byte n of a word (optionally doubled).  A wavefront issues about one instruction per five cycles whatever
+// the opcode, so the middle bytes use one v_bfe_u32 rather than a shift and a mask.
 template <int N, bool TIMES2 = false>
 __device__ __forceinline__ uint32_t byte_of(uint32_t w) {
   if constexpr (TIMES2) {
@@ -142,7 +143,11 @@ __device__ __forceinline__ uint32_t byte_of(uint32_t w) {
   } else {
     if constexpr (N == 0) return w & 0xffu;
     else if constexpr (N == 3) return w >> 24;
-    else return (w >> (8 * N)) & 0xffu;
+    else {
+      uint32_t r;
+      asm("v_bfe_u32 %0, %1, %2, 8" : "=v"(r) : "v"(w), "n"(8 * N));
+      return r;
+    }
   }
 }
 
@@ -229,15 +234,16 @@ __device__ __forceinline__ void consume_chunk(const uint32_t (&v)[8], const uint
   }
 }
 
-template <int K, int C>
-__device__ __forceinline__ void byte_pipeline(const uint32_t (&R)[4][8], const uint32_t (&xp)[16], const char* lds,
+// rows 2H, 2H+1 of the strip: chunk C = 2 * jj + rr uses buffer va; the next chunk is issued into vb first
+template <int K, int H, int C>
+__device__ __forceinline__ void byte_pipeline(const uint32_t (&R)[2][8], const uint32_t (&xp)[16], const char* lds,
                                               uint32_t (&va)[8], uint32_t (&vb)[8], float (&xf)[8], float (&acc)[8]) {
-  // chunk C = 4 * jj + r uses buffer va; the next chunk is issued into vb first
-  if constexpr (C < 16) {
-    constexpr int jj = C / 4, r = C % 4;
-    if constexpr (C + 1 < 16) issue_chunk<K, (C + 1) / 4>(R[(C + 1) % 4], lds + ((C + 1) % 4) * Decode<K>::row_bytes, vb);
+  if constexpr (C < 8) {
+    constexpr int jj = C / 2, rr = C % 2, row = 2 * H + rr;
+    if constexpr (C + 1 < 8)
+      issue_chunk<K, (C + 1) / 2>(R[(C + 1) % 2], lds + (2 * H + (C + 1) % 2) * Decode<K>::row_bytes, vb);
     sched_fence();
-    if constexpr (Decode<K>::scheme == Scheme::kF32 && r == 0) {
+    if constexpr (Decode<K>::scheme == Scheme::kF32 && rr == 0) {
 #pragma unroll
       for (int n = 0; n < 4; ++n) {
         half2_t xv = __builtin_bit_cast(half2_t, xp[4 * jj + n]);
@@ -246,10 +252,27 @@ __device__ __forceinline__ void byte_pipeline(const uint32_t (&R)[4][8], const u
       }
     }
     const uint32_t xp4[4] = {xp[4 * jj], xp[4 * jj + 1], xp[4 * jj + 2], xp[4 * jj + 3]};
-    consume_chunk<K>(va, xp4, xf, acc[2 * r], acc[2 * r + 1]);
+    consume_chunk<K>(va, xp4, xf, acc[2 * row], acc[2 * row + 1]);
     sched_fence();
-    byte_pipeline<K, C + 1>(R, xp, lds, vb, va, xf, acc);
+    byte_pipeline<K, H, C + 1>(R, xp, lds, vb, va, xf, acc);
   }
+}
+
+template <int K, int H>
+__device__ __forceinline__ void byte_rows(const PlaneStrip<K>& s, const uint32_t (&xp)[16], const char* lds,
+                                          float (&acc)[8]) {
+  uint32_t R[2][8];
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    uint32_t w[K];
+#pragma unroll
+    for (int b = 0; b < K; ++b) w[b] = s.w[b][2 * H + rr];
+    merge_byte_fields<K>(w, R[rr]);
+  }
+  uint32_t va[8], vb[8];
+  float xf[8];
+  issue_chunk<K, 0>(R[0], lds + 2 * H * Decode<K>::row_bytes, va);
+  byte_pipeline<K, H, 0>(R, xp, lds, va, vb, xf, acc);
 }
 
 // k = 3 chunk C = 2 * jj + half: rows 2 half, 2 half + 1, four pair lookups each
@@ -290,6 +313,15 @@ template <int K>
 __device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStrip& xs, int cw, int ncw, const char* lds,
                                               float (&acc)[8]) {
   if (cw >= ncw) return;
+#if defined(DPLLM_PROBE) && DPLLM_PROBE == 1
+  {
+    uint32_t z = 0;
+    for (int b = 0; b < K; ++b) z ^= s.w[b][0] ^ s.w[b][1] ^ s.w[b][2] ^ s.w[b][3];
+    for (int i = 0; i < 4; ++i) z ^= xs.x[i][0] ^ xs.x[i][1] ^ xs.x[i][2] ^ xs.x[i][3];
+    acc[0] += __builtin_bit_cast(float, z & 0x3f800000u);
+    return;
+  }
+#endif
   uint32_t xp[16];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -298,8 +330,8 @@ __device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStr
     xp[4 * i + 2] = xs.x[i].z;
     xp[4 * i + 3] = xs.x[i].w;
   }
-  uint32_t va[8], vb[8];
   if constexpr (K == 3) {
+    uint32_t va[8], vb[8];
     uint32_t T[4][4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -309,17 +341,8 @@ __device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStr
     issue_pair_chunk<0>(T, lds, va);
     pair_pipeline<0>(T, xp, lds, va, vb, acc);
   } else {
-    uint32_t R[4][8];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      uint32_t w[K];
-#pragma unroll
-      for (int b = 0; b < K; ++b) w[b] = s.w[b][r];
-      merge_byte_fields<K>(w, R[r]);
-    }
-    float xf[8];
-    issue_chunk<K, 0>(R[0], lds, va);
-    byte_pipeline<K, 0>(R, xp, lds, va, vb, xf, acc);
+    byte_rows<K, 0>(s, xp, lds, acc);
+    byte_rows<K, 1>(s, xp, lds, acc);
   }
 }
 
@@ -414,7 +437,7 @@ struct StreamState {
   XStrip xb[XS ? 2 : D];
   TableRegs<K> tr;
   float acc[8];
-  int rq0;
+  int rq0, stride;
   int lrq, lc0, lt;   // load cursor: row quad, first word of the strip, strip counter
   int crq, cc0, ct;   // compute cursor
   int total;
@@ -422,19 +445,23 @@ struct StreamState {
 
 template <int K, int D, bool XS, int I>
 __device__ __forceinline__ bool stream_step(StreamState<K, D, XS>& st, const GemvJob& job,
-                                            const DPLLM_GLOBAL uint16_t* lut_base, int rq1, int lane, char* lds) {
+                                            const DPLLM_GLOBAL uint16_t* lut_base, int rq_last, int lane, char* lds) {
   const int ncw = job.ncw;
   constexpr int slot = (I + D - 1) % D;
   {
     // past the end of the run the slot is refilled from the run's first strip (an L2 hit, never decoded)
     const bool more = st.lt < st.total;
     const int lrq = more ? st.lrq : st.rq0, lc0 = more ? st.lc0 : 0;
+#if !defined(DPLLM_PROBE) || DPLLM_PROBE != 2
     load_planes<K>(st.pb[slot], job, lrq, lc0 + lane);
     if constexpr (!XS) load_x(st.xb[slot], job, lc0 + lane);
+#else
+    for (int b = 0; b < K; ++b) st.pb[slot].w[b] ^= (uint32_t)(lrq * 0x9e3779b9u + lane);
+#endif
     if (more) {
       st.lt++;
       st.lc0 += 64;
-      if (st.lc0 >= ncw) { st.lc0 = 0; st.lrq++; }
+      if (st.lc0 >= ncw) { st.lc0 = 0; st.lrq += st.stride; }
     }
   }
   compute_strip<K>(st.pb[I], st.xb[XS ? (I & 1) : I], st.cc0 + lane, ncw, lds, st.acc);
@@ -442,11 +469,11 @@ __device__ __forceinline__ bool stream_step(StreamState<K, D, XS>& st, const Gem
   if (st.cc0 >= ncw) {
     finish_rowquad(job, st.crq, lane, st.acc);
     st.cc0 = 0;
-    st.crq++;
-    if (st.crq < rq1) {
+    st.crq += st.stride;
+    if (st.crq <= rq_last) {
       lds_order();
       store_tables<K>(st.tr, lds, lane);
-      fetch_tables<K>(st.tr, lut_base, min(st.crq + 1, rq1 - 1), lane);
+      fetch_tables<K>(st.tr, lut_base, min(st.crq + st.stride, rq_last), lane);
       lds_order();
     }
   }
@@ -455,23 +482,26 @@ __device__ __forceinline__ bool stream_step(StreamState<K, D, XS>& st, const Gem
 
 template <int K, int D, bool XS, int I>
 __device__ __forceinline__ bool stream_round(StreamState<K, D, XS>& st, const GemvJob& job,
-                                             const DPLLM_GLOBAL uint16_t* lut_base, int rq1, int lane, char* lds) {
+                                             const DPLLM_GLOBAL uint16_t* lut_base, int rq_last, int lane, char* lds) {
   if constexpr (I < D) {
-    if (stream_step<K, D, XS, I>(st, job, lut_base, rq1, lane, lds)) return true;
-    return stream_round<K, D, XS, I + 1>(st, job, lut_base, rq1, lane, lds);
+    if (stream_step<K, D, XS, I>(st, job, lut_base, rq_last, lane, lds)) return true;
+    return stream_round<K, D, XS, I + 1>(st, job, lut_base, rq_last, lane, lds);
   } else {
     return false;
   }
 }
 
 template <int K, int D, bool XS>
-__device__ __forceinline__ void gemv_stream(const GemvJob& job, uint32_t lut_off, int rq0, int rq1, int lane, char* lds) {
+__device__ __forceinline__ void gemv_stream(const GemvJob& job, uint32_t lut_off, int rq0, int stride, int nq, int lane,
+                                            char* lds) {
   const DPLLM_GLOBAL uint16_t* lut_base = as_global(reinterpret_cast<const uint16_t*>(job.arena + lut_off));
   const int ncw = job.ncw;
   StreamState<K, D, XS> st;
   const int ns = (ncw + 63) >> 6;
-  st.total = (rq1 - rq0) * ns;
+  const int rq_last = rq0 + (nq - 1) * stride;
+  st.total = nq * ns;
   st.rq0 = rq0;
+  st.stride = stride;
   st.lrq = rq0; st.lc0 = 0; st.lt = 0;
   st.crq = rq0; st.cc0 = 0; st.ct = 0;
 #pragma unroll
@@ -483,7 +513,7 @@ __device__ __forceinline__ void gemv_stream(const GemvJob& job, uint32_t lut_off
     if (more) {
       st.lt++;
       st.lc0 += 64;
-      if (st.lc0 >= ncw) { st.lc0 = 0; st.lrq++; }
+      if (st.lc0 >= ncw) { st.lc0 = 0; st.lrq += stride; }
     }
   }
   if constexpr (XS) {
@@ -492,39 +522,58 @@ __device__ __forceinline__ void gemv_stream(const GemvJob& job, uint32_t lut_off
   }
   fetch_tables<K>(st.tr, lut_base, rq0, lane);
   store_tables<K>(st.tr, lds, lane);
-  fetch_tables<K>(st.tr, lut_base, min(rq0 + 1, rq1 - 1), lane);
+  fetch_tables<K>(st.tr, lut_base, min(rq0 + stride, rq_last), lane);
   lds_order();
 #pragma unroll
   for (int r = 0; r < 8; ++r) st.acc[r] = 0.f;
-  while (!stream_round<K, D, XS, 0>(st, job, lut_base, rq1, lane, lds)) {
+  while (!stream_round<K, D, XS, 0>(st, job, lut_base, rq_last, lane, lds)) {
   }
 }
 
 template <int K>
-__device__ __forceinline__ void gemv_stream_any(const GemvJob& job, uint32_t lut_off, int rq0, int rq1, int lane, char* lds) {
+__device__ __forceinline__ void gemv_stream_any(const GemvJob& job, uint32_t lut_off, int rq0, int stride, int nq, int lane,
+                                                char* lds) {
+  // ring depth: as deep as about 160 registers per lane allow (three wavefronts per SIMD)
+#ifdef DPLLM_DEPTH_XS
+  constexpr int kDepthXS = DPLLM_DEPTH_XS;
+#else
+  constexpr int kDepthXS = K <= 3 ? 4 : (K <= 6 ? 3 : 2);
+#endif
+  constexpr int kDepthRing = K <= 5 ? 3 : 2;
   if (job.ncw > 64 && job.ncw <= 128)
-    gemv_stream<K, 4, true>(job, lut_off, rq0, rq1, lane, lds);
+    gemv_stream<K, kDepthXS, true>(job, lut_off, rq0, stride, nq, lane, lds);
   else
-    gemv_stream<K, 3, false>(job, lut_off, rq0, rq1, lane, lds);
+    gemv_stream<K, kDepthRing, false>(job, lut_off, rq0, stride, nq, lane, lds);
 }
 
 template <int KA, int KB>
 __device__ __forceinline__ void gemv_block(const GemvJob& job, int block, int lane, char* lds) {
-  const int rq0 = block * job.rq_per_block;
-  const int rq1 = min(job.nrq, rq0 + job.rq_per_block);
-  if (rq0 >= rq1) return;
+  // Workgroups that run at the same time take neighbouring row quads, so the chip reads one moving window
+  // of each plane instead of thousands of separate streams.
+#ifdef DPLLM_CONTIGUOUS_RUNS
+  const int per = (job.nrq + job.nblocks - 1) / job.nblocks;
+  const int rq0 = block * per, stride = 1;
+  const int nq = min(job.nrq, rq0 + per) - rq0;
+#else
+  const int rq0 = block, stride = job.nblocks;
+  const int nq = (job.nrq - block + job.nblocks - 1) / job.nblocks;
+#endif
+  if (nq <= 0) return;
   if constexpr (KA != KB) {
     if (job.k_dev != nullptr && __builtin_amdgcn_readfirstlane(*as_global(job.k_dev)) == KB) {
-      gemv_stream_any<KB>(job, job.lut_off_b, rq0, rq1, lane, lds);
+      gemv_stream_any<KB>(job, job.lut_off_b, rq0, stride, nq, lane, lds);
       return;
     }
   }
-  gemv_stream_any<KA>(job, job.lut_off_a, rq0, rq1, lane, lds);
+  gemv_stream_any<KA>(job, job.lut_off_a, rq0, stride, nq, lane, lds);
 }
 
 // jobs == nullptr: the single job passed by value; else block b belongs to the last job with block_start <= b
+#ifndef DPLLM_WAVES_PER_EU
+#define DPLLM_WAVES_PER_EU
+#endif
 template <int KA, int KB>
-__global__ void __launch_bounds__(64) gemv_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
+__global__ void __launch_bounds__(64) DPLLM_WAVES_PER_EU gemv_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
   __shared__ __attribute__((aligned(16))) char lds[lds_bytes<KA, KB>()];
   if (jobs == nullptr) {
     gemv_block<KA, KB>(one, blockIdx.x, threadIdx.x, lds);
