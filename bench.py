@@ -33,10 +33,12 @@ def selector_bytes(in_, r=RANK):
     return r * in_ * 2 + in_ * 2 + 8
 
 
-def build_model(dp, synth, torch, shapes, n_blocks, p, l, h, n_x, seed=1234, keep_blocks=(0,), log=None):
+def build_model(dp, synth, torch, shapes, n_blocks, p, l, h, n_x, seed=1234, keep_blocks=(0,), log=None,
+                quantile=None):
     """Loads n_blocks x len(shapes) linears generated on the GPU and attaches one projection selector each.
     Returns (model, meta) where meta carries shapes, thresholds, G, the activation sets and host copies of
-    the linears of `keep_blocks` for the oracle."""
+    the linears of `keep_blocks` for the oracle.  Thresholds: tau ~ U[0.05, 0.3] times the median of
+    ||W_h x|| (default), or the `quantile` of the calibration estimates."""
     import numpy as np
     n = n_blocks * len(shapes)
     model = dp.Model(n)
@@ -53,7 +55,10 @@ def build_model(dp, synth, torch, shapes, n_blocks, p, l, h, n_x, seed=1234, kee
             model.dpllm_load_linear(i, lin["planes"], lin["luts"], 3)
             G = synth.make_G(lin, l, h, RANK, seed=seed + 104729 * i + 1)
             est = synth.estimates_fp64(G, xs_by_in[in_])
-            T = synth.thresholds_from_tau(lin, h, xs_by_in[in_], float(taus[i]))
+            if quantile is None:
+                T = synth.thresholds_from_tau(lin, h, xs_by_in[in_], float(taus[i]))
+            else:   # Phase-3 style: the rho-quantile of the calibration estimates
+                T = synth.quantile_threshold(est, quantile)
             T = synth.nudge_threshold(T, est, band=1e-6)
             model.dpllm_set_selector(i, l, h, dp.DPLLM_SEL_PROJ, G=G, T=T)
             meta["shapes"].append((out, in_))

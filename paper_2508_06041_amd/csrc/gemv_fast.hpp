@@ -433,6 +433,7 @@ __device__ __forceinline__ void finish_rowquad(const GemvJob& job, int rq, int l
 // run.  XS = false: activations ride in a ring of their own, fetched with the planes (L2 hits).
 template <int K, int D, bool XS>
 struct StreamState {
+  static_assert(!XS || D % 2 == 0, "resident activations are picked by ring-slot parity");
   PlaneStrip<K> pb[D];
   XStrip xb[XS ? 2 : D];
   TableRegs<K> tr;
@@ -537,7 +538,7 @@ __device__ __forceinline__ void gemv_stream_any(const GemvJob& job, uint32_t lut
 #ifdef DPLLM_DEPTH_XS
   constexpr int kDepthXS = DPLLM_DEPTH_XS;
 #else
-  constexpr int kDepthXS = K <= 3 ? 4 : (K <= 6 ? 3 : 2);
+  constexpr int kDepthXS = K <= 3 ? 4 : 2;   // even: ring slot parity must equal strip parity
 #endif
   constexpr int kDepthRing = K <= 5 ? 3 : 2;
   if (job.ncw > 64 && job.ncw <= 128)
