@@ -135,7 +135,9 @@ SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* 
 
 // ---- GEMV -------------------------------------------------------------------------------------------------
 // Kernel instances: a fixed bitwidth k (k, k) and the adjacent candidate pairs (k, k + 1), k >= 3.  Anything
-// else (k < 3, non-adjacent pairs, batch > 1) is served by the plain kernel.
+// else (k < 3, non-adjacent pairs) is served by the plain kernel.  A batch of B right-hand sides runs as B
+// independent GEMVs inside one launch (the planes are streamed once per sample; the second to B-th pass
+// mostly hit the last-level cache).
 bool has_fast_kernel(int ka, int kb) { return ka >= 3 && kb <= 8 && (kb == ka || kb == ka + 1); }
 
 template <int KA, int KB>
@@ -210,11 +212,11 @@ int launch_plain(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_
 
 int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y,
                 int B, hipStream_t st) {
-  if (B != 1 || !has_fast_kernel(ka, kb)) return launch_plain(m, lin, ka, kb, k_dev, x, y, B, st);
+  if (!has_fast_kernel(ka, kb)) return launch_plain(m, lin, ka, kb, k_dev, x, y, B, st);
   GemvJob j = make_gemv_job(lin, ka, kb, k_dev, x, y);
   const int rpb = pick_rq_per_block(lin.L.nrq);
   j.nblocks = (lin.L.nrq + rpb - 1) / rpb;
-  launch_fast(ka, kb, nullptr, 1, j, j.nblocks, st);
+  launch_fast(ka, kb, nullptr, B, j, j.nblocks * B, st);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }

@@ -153,6 +153,11 @@ __device__ __forceinline__ uint32_t byte_of(uint32_t w) {
 
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 
+// Waits until at most N LDS operations of this wavefront are outstanding (global loads are not waited for).
+// One wait per chunk of lookups replaces the descending per-use waits the compiler would insert.
+template <int N>
+__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8)); }
+
 template <int K>
 struct PlaneStrip {
   u32x4 w[K];   // 4 rows x 32 columns of planes 0..K-1
@@ -243,6 +248,7 @@ __device__ __forceinline__ void byte_pipeline(const uint32_t (&R)[2][8], const u
     if constexpr (C + 1 < 8)
       issue_chunk<K, (C + 1) / 2>(R[(C + 1) % 2], lds + (2 * H + (C + 1) % 2) * Decode<K>::row_bytes, vb);
     sched_fence();
+    if constexpr (C + 1 < 8) wait_lds<8>(); else wait_lds<0>();
     if constexpr (Decode<K>::scheme == Scheme::kF32 && rr == 0) {
 #pragma unroll
       for (int n = 0; n < 4; ++n) {
@@ -297,6 +303,7 @@ __device__ __forceinline__ void pair_pipeline(const uint32_t (&T)[4][4], const u
     constexpr int jj = C / 2, r0 = 2 * (C % 2);
     if constexpr (C + 1 < 8) issue_pair_chunk<C + 1>(T, lds, vb);
     sched_fence();
+    if constexpr (C + 1 < 8) wait_lds<8>(); else wait_lds<0>();
 #pragma unroll
     for (int rr = 0; rr < 2; ++rr)
 #pragma unroll
@@ -569,7 +576,9 @@ __device__ __forceinline__ void gemv_block(const GemvJob& job, int block, int la
   gemv_stream_any<KA>(job, job.lut_off_a, rq0, stride, nq, lane, lds);
 }
 
-// jobs == nullptr: the single job passed by value; else block b belongs to the last job with block_start <= b
+// jobs == nullptr: the job passed by value, for njobs right-hand sides (sample s reads x + s * in and writes
+// y + s * out; workgroups [s * nblocks, (s + 1) * nblocks) serve it); else block b belongs to the last job of
+// the table whose block_start <= b
 #ifndef DPLLM_WAVES_PER_EU
 #define DPLLM_WAVES_PER_EU
 #endif
@@ -577,7 +586,10 @@ template <int KA, int KB>
 __global__ void __launch_bounds__(64) DPLLM_WAVES_PER_EU gemv_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
   __shared__ __attribute__((aligned(16))) char lds[lds_bytes<KA, KB>()];
   if (jobs == nullptr) {
-    gemv_block<KA, KB>(one, blockIdx.x, threadIdx.x, lds);
+    const int sample = blockIdx.x / one.nblocks;
+    one.x += (size_t)sample * one.ncw * 32;
+    one.y += (size_t)sample * one.out;
+    gemv_block<KA, KB>(one, blockIdx.x - sample * one.nblocks, threadIdx.x, lds);
     return;
   }
   const int b = blockIdx.x;
