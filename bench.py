@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--blocks", type=int, default=32, help="Transformer blocks (32 = the 7B shape)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-k sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--copy-yardstick", action="store_true",
+                    help="also run a plain 1 GiB copy kernel (for scaling hardware byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -98,6 +100,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_yardstick:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dp.dpllm_debug_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     shapes, p, l, h, n_x = synth.LLAMA_7B, 8, 3, 4, 256
     model, meta = build_model(dp, synth, torch, shapes, args.blocks, p, l, h, n_x, log=log)
     n = len(meta["shapes"])

@@ -145,6 +145,11 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
  * from the private device layout, to idx_dev (device).  Errors: EINVAL, ERANGE, ESTATE, EHIP. */
 int dpllm_debug_unpack(dpllm_model* m, int id, int k, uint8_t* idx_dev, void* stream);
 
+/* Measurement aid: a plain 128-bit copy kernel, bytes % 16 == 0, both pointers device and 16-byte
+ * aligned.  Its known traffic (bytes read + bytes written) scales the HBM byte counters that the
+ * profiles report for the GEMV.  Errors: EINVAL, EHIP. */
+int dpllm_debug_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -567,4 +567,11 @@ int dpllm_debug_unpack(dpllm_model* m, int id, int k, uint8_t* idx_dev, void* st
   return DPLLM_OK;
 }
 
+int dpllm_debug_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {
+  if (!dst_dev || !src_dev || bytes % 16 || ((uintptr_t)dst_dev | (uintptr_t)src_dev) % 16) return DPLLM_EINVAL;
+  hipLaunchKernelGGL(plain_copy_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src_dev,
+                     (uint4*)dst_dev, bytes / 16);
+  return hipGetLastError() == hipSuccess ? DPLLM_OK : DPLLM_EHIP;
+}
+
 }  // extern "C"

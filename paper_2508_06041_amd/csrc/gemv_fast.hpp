@@ -169,12 +169,17 @@ struct XStrip {
 // Loads are never predicated: a lane past the end of a ragged strip re-reads the last word (its result is
 // discarded at compute time).  Unconditional issue keeps the compiler's outstanding-load counts exact, so
 // it waits only for the strip it is about to decode and leaves the prefetched ones in flight.
+// `real` = false (ring slots past the end of the run): the K loads still issue, but from the activation
+// vector, which is hot in L2, so they cost no HBM traffic; the values are never decoded.
 template <int K>
-__device__ __forceinline__ void load_planes(PlaneStrip<K>& s, const GemvJob& job, int rq, int cw) {
+__device__ __forceinline__ void load_planes(PlaneStrip<K>& s, const GemvJob& job, int rq, int cw, bool real = true) {
   const int cwc = min(cw, job.ncw - 1);
-  const DPLLM_GLOBAL u32x4* p = as_global(reinterpret_cast<const u32x4*>(job.arena)) + (size_t)rq * job.ncw + cwc;
+  const DPLLM_GLOBAL u32x4* planes = as_global(reinterpret_cast<const u32x4*>(job.arena)) + (size_t)rq * job.ncw + cwc;
+  const DPLLM_GLOBAL u32x4* xs = as_global(reinterpret_cast<const u32x4*>(job.x)) + (size_t)cwc * 4;
+  const DPLLM_GLOBAL u32x4* p = real ? planes : xs;
+  const size_t step = real ? (size_t)job.plane_stride_u4 : 0;
 #pragma unroll
-  for (int b = 0; b < K; ++b) s.w[b] = load_stream(p + (size_t)b * job.plane_stride_u4);
+  for (int b = 0; b < K; ++b) s.w[b] = load_stream(p + (size_t)b * step);
 }
 
 __device__ __forceinline__ void load_x(XStrip& s, const GemvJob& job, int cw) {
@@ -457,11 +462,11 @@ __device__ __forceinline__ bool stream_step(StreamState<K, D, XS>& st, const Gem
   const int ncw = job.ncw;
   constexpr int slot = (I + D - 1) % D;
   {
-    // past the end of the run the slot is refilled from the run's first strip (an L2 hit, never decoded)
+    // past the end of the run the slot is refilled with dummy loads (see load_planes)
     const bool more = st.lt < st.total;
     const int lrq = more ? st.lrq : st.rq0, lc0 = more ? st.lc0 : 0;
 #if !defined(DPLLM_PROBE) || DPLLM_PROBE != 2
-    load_planes<K>(st.pb[slot], job, lrq, lc0 + lane);
+    load_planes<K>(st.pb[slot], job, lrq, lc0 + lane, more);
     if constexpr (!XS) load_x(st.xb[slot], job, lc0 + lane);
 #else
     for (int b = 0; b < K; ++b) st.pb[slot].w[b] ^= (uint32_t)(lrq * 0x9e3779b9u + lane);
@@ -516,7 +521,7 @@ __device__ __forceinline__ void gemv_stream(const GemvJob& job, uint32_t lut_off
   for (int i = 0; i < D - 1; ++i) {
     const bool more = st.lt < st.total;
     const int lrq = more ? st.lrq : rq0, lc0 = more ? st.lc0 : 0;
-    load_planes<K>(st.pb[i], job, lrq, lc0 + lane);
+    load_planes<K>(st.pb[i], job, lrq, lc0 + lane, more);
     if constexpr (!XS) load_x(st.xb[i], job, lc0 + lane);
     if (more) {
       st.lt++;
