@@ -162,6 +162,14 @@ def main():
     ms_sel = timed(lambda t: model.dpllm_decode_step_parts(xs, ys, k_dev, e_dev, dp.DPLLM_STEP_SELECT), args.steps, 5)
     sel_bytes = sum(selector_bytes(i) for _, i in meta["shapes"])
     roof_achieved = gemv_bytes0 / (ms_gemv * 1e-3) / 1e9
+    # HBM traffic per GEMV launch from the committed counter summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    # scaled by a plain copy kernel); it belongs to the default 32-block workload only
+    traffic = None
+    counters = os.path.join(ROOT, "profiles", "decode_step_7b_hbm_counters.txt")
+    if args.blocks == 32 and os.path.exists(counters):
+        for line in open(counters):
+            if line.startswith("gemv_traffic_bytes_per_launch"):
+                traffic = float(line.split()[1])
 
     # ---- per-k sweep, bitwidth pinned for every layer (the paper fixes it with +/-inf thresholds) -------
     per_k = {}
@@ -222,7 +230,8 @@ def main():
         "per_k": per_k,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel<3,4>", "achieved": round(roof_achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(roof_achieved / HBM_PEAK_GBPS, 4),
-                     "us_per_launch": round(ms_gemv * 1e3, 1), "traffic": None},
+                     "us_per_launch": round(ms_gemv * 1e3, 1), "algorithmic_bytes": int(gemv_bytes0),
+                     "traffic": traffic},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
