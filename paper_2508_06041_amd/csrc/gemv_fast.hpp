@@ -75,16 +75,18 @@ __device__ __forceinline__ DPLLM_GLOBAL T* as_global(T* p) { return (DPLLM_GLOBA
 __device__ __forceinline__ u32x4 load_stream(const DPLLM_GLOBAL u32x4* p) { return __builtin_nontemporal_load(p); }
 
 // ---- per-bitwidth decode scheme (all compile-time) ----------------------------------------------------
-// kPair : k = 3, byte = 4 * (8 a + b), table of fp16 pairs, v_dot2_f32_f16
-// kF32  : k <= 5, byte = code << 2, table of fp32 values, v_fma_f32 (activations converted once per strip)
+// kPair : k = 3, byte = 4 * (8 a + b); k = 4, byte = 16 a + b: table of fp16 pairs (LUT[a], LUT[b]), one
+//         v_dot2_f32_f16 per two weights
+// kF32  : k = 5, byte = code << 2, table of fp32 values, v_fma_f32 (activations converted once per strip)
 // kF16  : k >= 6, byte = code << 1 (k = 8: code), table of fp16 values, v_fma_mix_f32
 enum class Scheme { kPair, kF32, kF16 };
 template <int K>
 struct Decode {
-  static constexpr Scheme scheme = (K == 3) ? Scheme::kPair : (K <= 5 ? Scheme::kF32 : Scheme::kF16);
+  static constexpr Scheme scheme = (K <= 4) ? Scheme::kPair : (K <= 5 ? Scheme::kF32 : Scheme::kF16);
   static constexpr int shift = (scheme == Scheme::kF32) ? 2 : 1;        // log2 of the table entry size
   static constexpr int d = (K == 8) ? 0 : 8 - K - shift;                 // plane b uses merge-tree slot b + d
-  static constexpr int row_bytes = (K == 3) ? 256 : ((1 << K) << shift); // LDS bytes of one row's table
+  // LDS bytes of one row's table (pair tables: 4^k entries of 4 bytes)
+  static constexpr int row_bytes = (K == 3) ? 256 : (K == 4) ? 1024 : ((1 << K) << shift);
   // byte field of column `col`: which of the eight merged words, and which byte after the alignment rotation
   __host__ __device__ static constexpr int top(int col) { return (col_to_pos(col) + d) & 31; }
   __host__ __device__ static constexpr int word(int col) { return top(col) & 7; }
@@ -130,6 +132,38 @@ __device__ __forceinline__ void merge_pair_fields(const uint32_t (&w)[3], uint32
     const uint32_t m0 = rotl_c(0x90909090u, 2 * jj), m1 = rotl_c(0x48484848u, 2 * jj), m2 = rotl_c(0x24242424u, 2 * jj);
     uint32_t o = (w[0] & m0) | (w[1] & m1) | (w[2] & m2);
     T[jj] = jj ? __builtin_rotateright32(o, 2 * jj) : o;
+  }
+}
+
+// k = 4: planes of one row -> four words of four bytes 16 a + b.  Word c collects the 4-bit codes whose top
+// bit sits at a position congruent to c (mod 4) and is rotated so that codes fill whole nibbles; the two
+// weights of a byte are four positions apart.
+__device__ __forceinline__ void merge_nibble_pairs(const uint32_t (&w)[4], uint32_t (&T)[4]) {
+  uint32_t A[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    A[i][0] = bfi(field_mask(2, 0, 1), w[2 * i], w[2 * i + 1]);
+    A[i][1] = bfi(field_mask(2, 1, 1), w[2 * i], w[2 * i + 1]);
+  }
+  T[0] = __builtin_rotateright32(bfi(field_mask(4, 0, 2), A[0][0], A[1][0]), 1);
+  T[1] = __builtin_rotateright32(bfi(field_mask(4, 1, 2), A[0][1], A[1][1]), 2);
+  T[2] = __builtin_rotateright32(bfi(field_mask(4, 2, 2), A[0][0], A[1][0]), 3);
+  T[3] = bfi(field_mask(4, 3, 2), A[0][1], A[1][1]);
+}
+
+// columns of the two weights in byte m of word c of merge_nibble_pairs: upper nibble, lower nibble
+__host__ __device__ constexpr int nibble_pair_col_hi(int c, int m) { return pos_to_col((8 * m + 7 + ((c + 1) & 3)) & 31); }
+__host__ __device__ constexpr int nibble_pair_col_lo(int c, int m) { return pos_to_col((8 * m + 3 + ((c + 1) & 3)) & 31); }
+
+// activations re-paired to match merge_nibble_pairs: xq[4 c + m] = (x[col_hi], x[col_lo]), one v_perm_b32 each
+template <int I>
+__device__ __forceinline__ void nibble_pair_x(const uint32_t (&xp)[16], uint32_t (&xq)[16]) {
+  if constexpr (I < 16) {
+    constexpr int ca = nibble_pair_col_hi(I / 4, I % 4), cb = nibble_pair_col_lo(I / 4, I % 4);
+    constexpr uint32_t ba = 4 + 2 * (ca & 1), bb = 2 * (cb & 1);   // first byte of the wanted half in {src0, src1}
+    constexpr uint32_t sel = ba | ((ba + 1) << 8) | (bb << 16) | ((bb + 1) << 24);
+    xq[I] = __builtin_amdgcn_perm(xp[ca / 2], xp[cb / 2], sel);
+    nibble_pair_x<I + 1>(xp, xq);
   }
 }
 
@@ -202,7 +236,8 @@ template <int K>
 __host__ __device__ constexpr int row_table_bytes() { return Decode<K>::row_bytes; }
 template <int KA, int KB>
 __host__ __device__ constexpr int lds_bytes() {
-  return 4 * (row_table_bytes<KA>() > row_table_bytes<KB>() ? row_table_bytes<KA>() : row_table_bytes<KB>());
+  // + 128: staging area of the k = 4 raw tables
+  return 4 * (row_table_bytes<KA>() > row_table_bytes<KB>() ? row_table_bytes<KA>() : row_table_bytes<KB>()) + 128;
 }
 
 // Lookups run as a software pipeline of chunks of 8: the LDS reads of chunk c+1 are issued before the
@@ -286,27 +321,35 @@ __device__ __forceinline__ void byte_rows(const PlaneStrip<K>& s, const uint32_t
   byte_pipeline<K, H, 0>(R, xp, lds, va, vb, xf, acc);
 }
 
-// k = 3 chunk C = 2 * jj + half: rows 2 half, 2 half + 1, four pair lookups each
-template <int C>
+// LDS offset of the pair entry named by byte n of a merged word: k = 3 bytes are pre-scaled, k = 4 bytes are
+// entry numbers (the compiler selects the byte and scales it in one SDWA shift)
+template <int K, int N>
+__device__ __forceinline__ uint32_t pair_offset(uint32_t t) {
+  if constexpr (K == 3) return byte_of<N>(t);
+  else return ((t >> (8 * N)) & 0xffu) << 2;
+}
+
+// pair schemes, chunk C = 2 * jj + half: rows 2 half, 2 half + 1, four pair lookups each from word jj
+template <int K, int C>
 __device__ __forceinline__ void issue_pair_chunk(const uint32_t (&T)[4][4], const char* lds, uint32_t (&v)[8]) {
   constexpr int jj = C / 2, r0 = 2 * (C % 2);
 #pragma unroll
   for (int rr = 0; rr < 2; ++rr) {
     const uint32_t t = T[r0 + rr][jj];
-    const char* tbl = lds + (r0 + rr) * 256;
-    v[4 * rr + 0] = *reinterpret_cast<const uint32_t*>(tbl + byte_of<0>(t));
-    v[4 * rr + 1] = *reinterpret_cast<const uint32_t*>(tbl + byte_of<1>(t));
-    v[4 * rr + 2] = *reinterpret_cast<const uint32_t*>(tbl + byte_of<2>(t));
-    v[4 * rr + 3] = *reinterpret_cast<const uint32_t*>(tbl + byte_of<3>(t));
+    const char* tbl = lds + (r0 + rr) * Decode<K>::row_bytes;
+    v[4 * rr + 0] = *reinterpret_cast<const uint32_t*>(tbl + pair_offset<K, 0>(t));
+    v[4 * rr + 1] = *reinterpret_cast<const uint32_t*>(tbl + pair_offset<K, 1>(t));
+    v[4 * rr + 2] = *reinterpret_cast<const uint32_t*>(tbl + pair_offset<K, 2>(t));
+    v[4 * rr + 3] = *reinterpret_cast<const uint32_t*>(tbl + pair_offset<K, 3>(t));
   }
 }
 
-template <int C>
+template <int K, int C>
 __device__ __forceinline__ void pair_pipeline(const uint32_t (&T)[4][4], const uint32_t (&xp)[16], const char* lds,
                                               uint32_t (&va)[8], uint32_t (&vb)[8], float (&acc)[8]) {
   if constexpr (C < 8) {
     constexpr int jj = C / 2, r0 = 2 * (C % 2);
-    if constexpr (C + 1 < 8) issue_pair_chunk<C + 1>(T, lds, vb);
+    if constexpr (C + 1 < 8) issue_pair_chunk<K, C + 1>(T, lds, vb);
     sched_fence();
     if constexpr (C + 1 < 8) wait_lds<8>(); else wait_lds<0>();
 #pragma unroll
@@ -317,7 +360,7 @@ __device__ __forceinline__ void pair_pipeline(const uint32_t (&T)[4][4], const u
         a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, va[4 * rr + n]), __builtin_bit_cast(half2_t, xp[4 * jj + n]), a, false);
       }
     sched_fence();
-    pair_pipeline<C + 1>(T, xp, lds, vb, va, acc);
+    pair_pipeline<K, C + 1>(T, xp, lds, vb, va, acc);
   }
 }
 
@@ -350,8 +393,19 @@ __device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStr
       const uint32_t w[3] = {s.w[0][r], s.w[1][r], s.w[2][r]};
       merge_pair_fields(w, T[r]);
     }
-    issue_pair_chunk<0>(T, lds, va);
-    pair_pipeline<0>(T, xp, lds, va, vb, acc);
+    issue_pair_chunk<3, 0>(T, lds, va);
+    pair_pipeline<3, 0>(T, xp, lds, va, vb, acc);
+  } else if constexpr (K == 4) {
+    uint32_t va[8], vb[8];
+    uint32_t T[4][4], xq[16];
+    nibble_pair_x<0>(xp, xq);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t w[4] = {s.w[0][r], s.w[1][r], s.w[2][r], s.w[3][r]};
+      merge_nibble_pairs(w, T[r]);
+    }
+    issue_pair_chunk<4, 0>(T, lds, va);
+    pair_pipeline<4, 0>(T, xq, lds, va, vb, acc);
   } else {
     byte_rows<K, 0>(s, xp, lds, acc);
     byte_rows<K, 1>(s, xp, lds, acc);
@@ -361,9 +415,10 @@ __device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStr
 // The tables of one row quad, fetched one row quad ahead into registers and written to LDS at the boundary.
 template <int K>
 struct TableRegs {
-  // per lane: k = 3 one pair entry per row; fp32 tables one entry per register; fp16 tables two
+  // per lane: k = 3 one pair entry per row; k = 4 one dword of the raw tables (the pair entries are formed
+  // at store time); fp32 tables one entry per register; fp16 tables two
   static constexpr int kEntries = 4 << K;  // table entries of a row quad
-  static constexpr int kDwords = (K == 3) ? 4
+  static constexpr int kDwords = (K == 3) ? 4 : (K == 4) ? 1
                                : (Decode<K>::scheme == Scheme::kF32 ? (kEntries + 63) / 64 : (kEntries / 2 + 63) / 64);
   uint32_t v[kDwords];
 };
@@ -375,6 +430,8 @@ __device__ __forceinline__ void fetch_tables(TableRegs<K>& t, const DPLLM_GLOBAL
     const int a = lane >> 3, b = lane & 7;
 #pragma unroll
     for (int r = 0; r < 4; ++r) t.v[r] = (uint32_t)lut[r * 8 + a] | ((uint32_t)lut[r * 8 + b] << 16);
+  } else if constexpr (K == 4) {
+    t.v[0] = reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(lut)[lane & 31];   // 4 rows x 16 fp16 = 32 dwords
   } else if constexpr (Decode<K>::scheme == Scheme::kF32) {
     constexpr int entries = TableRegs<K>::kEntries;
 #pragma unroll
@@ -399,6 +456,24 @@ __device__ __forceinline__ void store_tables(const TableRegs<K>& t, char* lds, i
   if constexpr (K == 3) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) dst[r * 64 + lane] = t.v[r];
+  } else if constexpr (K == 4) {
+    // the raw tables go to a 128-byte staging area behind the four pair tables; lane (g, b) = (lane / 16,
+    // lane % 16) then forms the entries (a, b), a = 4 g .. 4 g + 3, of every row
+    uint32_t* raw = dst + 4 * (Decode<4>::row_bytes / 4);
+    if (lane < 32) raw[lane] = t.v[0];
+    lds_order();
+    const int b = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint16_t* row = reinterpret_cast<const uint16_t*>(raw) + r * 16;
+      const uint32_t lb = (uint32_t)row[b] << 16;
+      const u32x2 la = *reinterpret_cast<const u32x2*>(row + 4 * g);
+      uint32_t* out = dst + r * 256 + 64 * g + b;
+      out[0] = (la.x & 0xffffu) | lb;
+      out[16] = (la.x >> 16) | lb;
+      out[32] = (la.y & 0xffffu) | lb;
+      out[48] = (la.y >> 16) | lb;
+    }
   } else if constexpr (Decode<K>::scheme == Scheme::kF32) {
     constexpr int entries = TableRegs<K>::kEntries;
 #pragma unroll
