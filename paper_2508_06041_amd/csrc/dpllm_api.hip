@@ -135,14 +135,27 @@ SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* 
 
 // ---- GEMV -------------------------------------------------------------------------------------------------
 // Kernel instances: a fixed bitwidth k (k, k) and the adjacent candidate pairs (k, k + 1), k >= 3.  Anything
-// else (k < 3, non-adjacent pairs) is served by the plain kernel.  A batch of B right-hand sides runs as B
-// independent GEMVs inside one launch (the planes are streamed once per sample; the second to B-th pass
-// mostly hit the last-level cache).
+// else (k < 3, non-adjacent pairs) is served by the plain kernel.  A batch of B right-hand sides runs in
+// groups of two (B = 2) or four samples inside one launch; a group decodes every weight once and multiplies it
+// with each of its samples.
 bool has_fast_kernel(int ka, int kb) { return ka >= 3 && kb <= 8 && (kb == ka || kb == ka + 1); }
+
+// Right-hand sides that share one pass over the planes.  A batch B runs as ceil(B / group) groups.
+template <int KA, int KB, int NB>
+void launch_group_t(int njobs, const GemvJob& one, hipStream_t st) {
+  const int groups = (njobs + NB - 1) / NB;
+  hipLaunchKernelGGL((gemv_kernel<KA, KB, NB>), dim3(one.nblocks * groups), dim3(64), 0, st, (const GemvJob*)nullptr, njobs, one);
+}
 
 template <int KA, int KB>
 void launch_fast_t(const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
-  hipLaunchKernelGGL((gemv_kernel<KA, KB>), dim3(blocks), dim3(64), 0, st, d_jobs, njobs, one);
+  if (d_jobs == nullptr && njobs > 1) {
+    // measured on 8B shapes: two samples per pass are fastest for B = 2, four per pass from B = 3 on
+    if (njobs == 2) launch_group_t<KA, KB, 2>(njobs, one, st);
+    else launch_group_t<KA, KB, 4>(njobs, one, st);
+  } else {
+    hipLaunchKernelGGL((gemv_kernel<KA, KB, 1>), dim3(blocks), dim3(64), 0, st, d_jobs, njobs, one);
+  }
 }
 
 void launch_fast(int ka, int kb, const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
@@ -168,6 +181,7 @@ GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, c
   j.out = lin.L.out; j.ncw = lin.L.ncw; j.nrq = lin.L.nrq;
   j.nblocks = lin.L.nrq;
   j.block_start = 0;
+  j.nsamples = 1;
   return j;
 }
 

@@ -43,6 +43,7 @@ struct GemvJob {
   int32_t out, ncw, nrq;
   int32_t nblocks;            // workgroups of this job; workgroup b streams row quads b, b + nblocks, ...
   int32_t block_start;        // index of this job's first workgroup inside a multi-job grid
+  int32_t nsamples;           // right-hand sides served together (1..NB): sample s reads x + s * in, writes y + s * out
 };
 
 __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
@@ -197,8 +198,9 @@ template <int K>
 struct PlaneStrip {
   u32x4 w[K];   // 4 rows x 32 columns of planes 0..K-1
 };
+template <int NB>
 struct XStrip {
-  u32x4 x[4];   // the lane's 32 activations as 16 fp16 pairs
+  u32x4 x[NB][4];   // per right-hand side: the lane's 32 activations as 16 fp16 pairs
 };
 
 // Loads are never predicated: a lane past the end of a ragged strip re-reads the last word (its result is
@@ -217,11 +219,17 @@ __device__ __forceinline__ void load_planes(PlaneStrip<K>& s, const GemvJob& job
   for (int b = 0; b < K; ++b) s.w[b] = load_stream(p + (size_t)b * step);
 }
 
-__device__ __forceinline__ void load_x(XStrip& s, const GemvJob& job, int cw) {
+template <int NB>
+__device__ __forceinline__ void load_x(XStrip<NB>& s, const GemvJob& job, int cw) {
   const int cwc = min(cw, job.ncw - 1);
-  const DPLLM_GLOBAL u32x4* xp = as_global(reinterpret_cast<const u32x4*>(job.x)) + (size_t)cwc * 4;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) s.x[i] = xp[i];
+  for (int b = 0; b < NB; ++b) {
+    // a group with fewer than NB samples re-reads its last one (the sums are not stored)
+    const int sample = NB == 1 ? 0 : min(b, job.nsamples - 1);
+    const DPLLM_GLOBAL u32x4* xp = as_global(reinterpret_cast<const u32x4*>(job.x)) + ((size_t)sample * job.ncw + cwc) * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s.x[b][i] = xp[i];
+  }
 }
 
 // Orders the LDS table writes of a wavefront against its own lookups.  A workgroup is a single wavefront and
@@ -264,7 +272,7 @@ __device__ __forceinline__ void issue_chunk(const uint32_t (&R)[8], const char* 
 }
 
 template <int K>
-__device__ __forceinline__ void consume_chunk(const uint32_t (&v)[8], const uint32_t (&xp4)[4], const float (&xf)[8],
+__device__ __forceinline__ void consume_chunk(const uint32_t (&v)[8], const uint32_t* xp4, const float (&xf)[8],
                                               float& acc0, float& acc1) {
   using D = Decode<K>;
 #pragma unroll
@@ -281,33 +289,35 @@ __device__ __forceinline__ void consume_chunk(const uint32_t (&v)[8], const uint
 }
 
 // rows 2H, 2H+1 of the strip: chunk C = 2 * jj + rr uses buffer va; the next chunk is issued into vb first
-template <int K, int H, int C>
-__device__ __forceinline__ void byte_pipeline(const uint32_t (&R)[2][8], const uint32_t (&xp)[16], const char* lds,
-                                              uint32_t (&va)[8], uint32_t (&vb)[8], float (&xf)[8], float (&acc)[8]) {
+template <int K, int NB, int H, int C>
+__device__ __forceinline__ void byte_pipeline(const uint32_t (&R)[2][8], const uint32_t (&xp)[NB][16], const char* lds,
+                                              uint32_t (&va)[8], uint32_t (&vb)[8], float (&xf)[NB][8], float (&acc)[NB][8]) {
   if constexpr (C < 8) {
     constexpr int jj = C / 2, rr = C % 2, row = 2 * H + rr;
     if constexpr (C + 1 < 8)
       issue_chunk<K, (C + 1) / 2>(R[(C + 1) % 2], lds + (2 * H + (C + 1) % 2) * Decode<K>::row_bytes, vb);
     sched_fence();
     if constexpr (C + 1 < 8) wait_lds<8>(); else wait_lds<0>();
-    if constexpr (Decode<K>::scheme == Scheme::kF32 && rr == 0) {
 #pragma unroll
-      for (int n = 0; n < 4; ++n) {
-        half2_t xv = __builtin_bit_cast(half2_t, xp[4 * jj + n]);
-        xf[2 * n] = (float)xv.x;
-        xf[2 * n + 1] = (float)xv.y;
+    for (int b = 0; b < NB; ++b) {
+      if constexpr (Decode<K>::scheme == Scheme::kF32 && rr == 0) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+          half2_t xv = __builtin_bit_cast(half2_t, xp[b][4 * jj + n]);
+          xf[b][2 * n] = (float)xv.x;
+          xf[b][2 * n + 1] = (float)xv.y;
+        }
       }
+      consume_chunk<K>(va, &xp[b][4 * jj], xf[b], acc[b][2 * row], acc[b][2 * row + 1]);
     }
-    const uint32_t xp4[4] = {xp[4 * jj], xp[4 * jj + 1], xp[4 * jj + 2], xp[4 * jj + 3]};
-    consume_chunk<K>(va, xp4, xf, acc[2 * row], acc[2 * row + 1]);
     sched_fence();
-    byte_pipeline<K, H, C + 1>(R, xp, lds, vb, va, xf, acc);
+    byte_pipeline<K, NB, H, C + 1>(R, xp, lds, vb, va, xf, acc);
   }
 }
 
-template <int K, int H>
-__device__ __forceinline__ void byte_rows(const PlaneStrip<K>& s, const uint32_t (&xp)[16], const char* lds,
-                                          float (&acc)[8]) {
+template <int K, int NB, int H>
+__device__ __forceinline__ void byte_rows(const PlaneStrip<K>& s, const uint32_t (&xp)[NB][16], const char* lds,
+                                          float (&acc)[NB][8]) {
   uint32_t R[2][8];
 #pragma unroll
   for (int rr = 0; rr < 2; ++rr) {
@@ -317,9 +327,9 @@ __device__ __forceinline__ void byte_rows(const PlaneStrip<K>& s, const uint32_t
     merge_byte_fields<K>(w, R[rr]);
   }
   uint32_t va[8], vb[8];
-  float xf[8];
+  float xf[NB][8];
   issue_chunk<K, 0>(R[0], lds + 2 * H * Decode<K>::row_bytes, va);
-  byte_pipeline<K, H, 0>(R, xp, lds, va, vb, xf, acc);
+  byte_pipeline<K, NB, H, 0>(R, xp, lds, va, vb, xf, acc);
 }
 
 // LDS offset of the pair entry named by byte n of a merged word: k = 3 bytes are pre-scaled, k = 4 bytes are
@@ -345,38 +355,42 @@ __device__ __forceinline__ void issue_pair_chunk(const uint32_t (&T)[4][4], cons
   }
 }
 
-template <int K, int C>
-__device__ __forceinline__ void pair_pipeline(const uint32_t (&T)[4][4], const uint32_t (&xp)[16], const char* lds,
-                                              uint32_t (&va)[8], uint32_t (&vb)[8], float (&acc)[8]) {
+template <int K, int NB, int C>
+__device__ __forceinline__ void pair_pipeline(const uint32_t (&T)[4][4], const uint32_t (&xp)[NB][16], const char* lds,
+                                              uint32_t (&va)[8], uint32_t (&vb)[8], float (&acc)[NB][8]) {
   if constexpr (C < 8) {
     constexpr int jj = C / 2, r0 = 2 * (C % 2);
     if constexpr (C + 1 < 8) issue_pair_chunk<K, C + 1>(T, lds, vb);
     sched_fence();
     if constexpr (C + 1 < 8) wait_lds<8>(); else wait_lds<0>();
 #pragma unroll
-    for (int rr = 0; rr < 2; ++rr)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int n = 0; n < 4; ++n) {
-        float& a = acc[2 * (r0 + rr) + (n & 1)];
-        a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, va[4 * rr + n]), __builtin_bit_cast(half2_t, xp[4 * jj + n]), a, false);
-      }
+      for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+          float& a = acc[b][2 * (r0 + rr) + (n & 1)];
+          a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, va[4 * rr + n]), __builtin_bit_cast(half2_t, xp[b][4 * jj + n]), a, false);
+        }
     sched_fence();
-    pair_pipeline<K, C + 1>(T, xp, lds, vb, va, acc);
+    pair_pipeline<K, NB, C + 1>(T, xp, lds, vb, va, acc);
   }
 }
 
-template <int K>
-__device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStrip& xs, int cw, int ncw, const char* lds,
-                                              float (&acc)[8]) {
+template <int K, int NB>
+__device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStrip<NB>& xs, int cw, int ncw, const char* lds,
+                                              float (&acc)[NB][8]) {
   if (cw >= ncw) return;
-  uint32_t xp[16];
+  uint32_t xp[NB][16];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    xp[4 * i + 0] = xs.x[i].x;
-    xp[4 * i + 1] = xs.x[i].y;
-    xp[4 * i + 2] = xs.x[i].z;
-    xp[4 * i + 3] = xs.x[i].w;
-  }
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      xp[b][4 * i + 0] = xs.x[b][i].x;
+      xp[b][4 * i + 1] = xs.x[b][i].y;
+      xp[b][4 * i + 2] = xs.x[b][i].z;
+      xp[b][4 * i + 3] = xs.x[b][i].w;
+    }
   if constexpr (K == 3) {
     uint32_t va[8], vb[8];
     uint32_t T[4][4];
@@ -386,21 +400,22 @@ __device__ __forceinline__ void compute_strip(const PlaneStrip<K>& s, const XStr
       merge_pair_fields(w, T[r]);
     }
     issue_pair_chunk<3, 0>(T, lds, va);
-    pair_pipeline<3, 0>(T, xp, lds, va, vb, acc);
+    pair_pipeline<3, NB, 0>(T, xp, lds, va, vb, acc);
   } else if constexpr (K == 4) {
     uint32_t va[8], vb[8];
-    uint32_t T[4][4], xq[16];
-    nibble_pair_x<0>(xp, xq);
+    uint32_t T[4][4], xq[NB][16];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) nibble_pair_x<0>(xp[b], xq[b]);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const uint32_t w[4] = {s.w[0][r], s.w[1][r], s.w[2][r], s.w[3][r]};
       merge_nibble_pairs(w, T[r]);
     }
     issue_pair_chunk<4, 0>(T, lds, va);
-    pair_pipeline<4, 0>(T, xq, lds, va, vb, acc);
+    pair_pipeline<4, NB, 0>(T, xq, lds, va, vb, acc);
   } else {
-    byte_rows<K, 0>(s, xp, lds, acc);
-    byte_rows<K, 1>(s, xp, lds, acc);
+    byte_rows<K, NB, 0>(s, xp, lds, acc);
+    byte_rows<K, NB, 1>(s, xp, lds, acc);
   }
 }
 
@@ -484,23 +499,27 @@ __device__ __forceinline__ void store_tables(const TableRegs<K>& t, char* lds, i
   }
 }
 
-__device__ __forceinline__ void finish_rowquad(const GemvJob& job, int rq, int lane, float (&acc)[8]) {
-  float s[4];
+template <int NB>
+__device__ __forceinline__ void finish_rowquad(const GemvJob& job, int rq, int lane, float (&acc)[NB][8]) {
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    s[r] = wave_sum_to_lane63(acc[2 * r] + acc[2 * r + 1]);
-    acc[2 * r] = acc[2 * r + 1] = 0.f;
-  }
-  if (lane == 63) {
-    half2_t lo = {(_Float16)s[0], (_Float16)s[1]}, hi = {(_Float16)s[2], (_Float16)s[3]};
-    DPLLM_GLOBAL uint16_t* y = as_global(job.y) + (size_t)rq * 4;
-    if (rq * 4 + 4 <= job.out && (reinterpret_cast<uintptr_t>(job.y) & 7) == 0) {
-      u32x2 v = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
-      *reinterpret_cast<DPLLM_GLOBAL u32x2*>(y) = v;
-    } else {
+  for (int b = 0; b < NB; ++b) {
+    float s[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (rq * 4 + r < job.out) y[r] = __builtin_bit_cast(uint16_t, (_Float16)s[r]);
+    for (int r = 0; r < 4; ++r) {
+      s[r] = wave_sum_to_lane63(acc[b][2 * r] + acc[b][2 * r + 1]);
+      acc[b][2 * r] = acc[b][2 * r + 1] = 0.f;
+    }
+    if (lane == 63 && (NB == 1 || b < job.nsamples)) {
+      half2_t lo = {(_Float16)s[0], (_Float16)s[1]}, hi = {(_Float16)s[2], (_Float16)s[3]};
+      DPLLM_GLOBAL uint16_t* y = as_global(job.y) + (size_t)b * job.out + (size_t)rq * 4;
+      if (rq * 4 + 4 <= job.out && (reinterpret_cast<uintptr_t>(y) & 7) == 0) {
+        u32x2 v = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+        *reinterpret_cast<DPLLM_GLOBAL u32x2*>(y) = v;
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (rq * 4 + r < job.out) y[r] = __builtin_bit_cast(uint16_t, (_Float16)s[r]);
+      }
     }
   }
 }
@@ -510,21 +529,21 @@ __device__ __forceinline__ void finish_rowquad(const GemvJob& job, int rq, int l
 // is several microseconds, so about 100 KiB per compute unit must be in flight to keep the memory busy).
 // XS = true (exactly two strips per row): the activations of both strips stay in registers for the whole
 // run.  XS = false: activations ride in a ring of their own, fetched with the planes (L2 hits).
-template <int K, int D, bool XS>
+template <int K, int D, bool XS, int NB>
 struct StreamState {
   static_assert(!XS || D % 2 == 0, "resident activations are picked by ring-slot parity");
   PlaneStrip<K> pb[D];
-  XStrip xb[XS ? 2 : D];
+  XStrip<NB> xb[XS ? 2 : D];
   TableRegs<K> tr;
-  float acc[8];
+  float acc[NB][8];
   int rq0, stride;
   int lrq, lc0, lt;   // load cursor: row quad, first word of the strip, strip counter
   int crq, cc0, ct;   // compute cursor
   int total;
 };
 
-template <int K, int D, bool XS, int I>
-__device__ __forceinline__ bool stream_step(StreamState<K, D, XS>& st, const GemvJob& job,
+template <int K, int D, bool XS, int NB, int I>
+__device__ __forceinline__ bool stream_step(StreamState<K, D, XS, NB>& st, const GemvJob& job,
                                             const DPLLM_GLOBAL uint16_t* lut_base, int rq_last, int lane, char* lds) {
   const int ncw = job.ncw;
   constexpr int slot = (I + D - 1) % D;
@@ -540,10 +559,10 @@ __device__ __forceinline__ bool stream_step(StreamState<K, D, XS>& st, const Gem
       if (st.lc0 >= ncw) { st.lc0 = 0; st.lrq += st.stride; }
     }
   }
-  compute_strip<K>(st.pb[I], st.xb[XS ? (I & 1) : I], st.cc0 + lane, ncw, lds, st.acc);
+  compute_strip<K, NB>(st.pb[I], st.xb[XS ? (I & 1) : I], st.cc0 + lane, ncw, lds, st.acc);
   st.cc0 += 64;
   if (st.cc0 >= ncw) {
-    finish_rowquad(job, st.crq, lane, st.acc);
+    finish_rowquad<NB>(job, st.crq, lane, st.acc);
     st.cc0 = 0;
     st.crq += st.stride;
     if (st.crq <= rq_last) {
@@ -556,23 +575,23 @@ __device__ __forceinline__ bool stream_step(StreamState<K, D, XS>& st, const Gem
   return ++st.ct == st.total;
 }
 
-template <int K, int D, bool XS, int I>
-__device__ __forceinline__ bool stream_round(StreamState<K, D, XS>& st, const GemvJob& job,
+template <int K, int D, bool XS, int NB, int I>
+__device__ __forceinline__ bool stream_round(StreamState<K, D, XS, NB>& st, const GemvJob& job,
                                              const DPLLM_GLOBAL uint16_t* lut_base, int rq_last, int lane, char* lds) {
   if constexpr (I < D) {
-    if (stream_step<K, D, XS, I>(st, job, lut_base, rq_last, lane, lds)) return true;
-    return stream_round<K, D, XS, I + 1>(st, job, lut_base, rq_last, lane, lds);
+    if (stream_step<K, D, XS, NB, I>(st, job, lut_base, rq_last, lane, lds)) return true;
+    return stream_round<K, D, XS, NB, I + 1>(st, job, lut_base, rq_last, lane, lds);
   } else {
     return false;
   }
 }
 
-template <int K, int D, bool XS>
+template <int K, int D, bool XS, int NB>
 __device__ __forceinline__ void gemv_stream(const GemvJob& job, uint32_t lut_off, int rq0, int stride, int nq, int lane,
                                             char* lds) {
   const DPLLM_GLOBAL uint16_t* lut_base = as_global(reinterpret_cast<const uint16_t*>(job.arena + lut_off));
   const int ncw = job.ncw;
-  StreamState<K, D, XS> st;
+  StreamState<K, D, XS, NB> st;
   const int ns = (ncw + 63) >> 6;
   const int rq_last = rq0 + (nq - 1) * stride;
   st.total = nq * ns;
@@ -601,25 +620,28 @@ __device__ __forceinline__ void gemv_stream(const GemvJob& job, uint32_t lut_off
   fetch_tables<K>(st.tr, lut_base, min(rq0 + stride, rq_last), lane);
   lds_order();
 #pragma unroll
-  for (int r = 0; r < 8; ++r) st.acc[r] = 0.f;
-  while (!stream_round<K, D, XS, 0>(st, job, lut_base, rq_last, lane, lds)) {
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int r = 0; r < 8; ++r) st.acc[b][r] = 0.f;
+  while (!stream_round<K, D, XS, NB, 0>(st, job, lut_base, rq_last, lane, lds)) {
   }
 }
 
-template <int K>
+template <int K, int NB>
 __device__ __forceinline__ void gemv_stream_any(const GemvJob& job, uint32_t lut_off, int rq0, int stride, int nq, int lane,
                                                 char* lds) {
   // Ring depth 2 (one strip in flight behind the one being decoded) measured best at every k: deeper rings
   // cost registers (hence resident wavefronts) and put more requests in flight than the memory system likes.
   constexpr int kDepthXS = 2;   // even: ring slot parity must equal strip parity
   constexpr int kDepthRing = 2;
-  if (job.ncw > 64 && job.ncw <= 128)
-    gemv_stream<K, kDepthXS, true>(job, lut_off, rq0, stride, nq, lane, lds);
+  // several right-hand sides: their activations always ride the ring (registers)
+  if (NB == 1 && job.ncw > 64 && job.ncw <= 128)
+    gemv_stream<K, kDepthXS, NB == 1, NB>(job, lut_off, rq0, stride, nq, lane, lds);
   else
-    gemv_stream<K, kDepthRing, false>(job, lut_off, rq0, stride, nq, lane, lds);
+    gemv_stream<K, kDepthRing, false, NB>(job, lut_off, rq0, stride, nq, lane, lds);
 }
 
-template <int KA, int KB>
+template <int KA, int KB, int NB>
 __device__ __forceinline__ void gemv_block(const GemvJob& job, int block, int lane, char* lds) {
   // Workgroups that run at the same time take neighbouring row quads, so the chip reads one moving window
   // of each plane instead of thousands of separate streams.
@@ -628,34 +650,38 @@ __device__ __forceinline__ void gemv_block(const GemvJob& job, int block, int la
   if (nq <= 0) return;
   if constexpr (KA != KB) {
     if (job.k_dev != nullptr && __builtin_amdgcn_readfirstlane(*as_global(job.k_dev)) == KB) {
-      gemv_stream_any<KB>(job, job.lut_off_b, rq0, stride, nq, lane, lds);
+      gemv_stream_any<KB, NB>(job, job.lut_off_b, rq0, stride, nq, lane, lds);
       return;
     }
   }
-  gemv_stream_any<KA>(job, job.lut_off_a, rq0, stride, nq, lane, lds);
+  gemv_stream_any<KA, NB>(job, job.lut_off_a, rq0, stride, nq, lane, lds);
 }
 
-// jobs == nullptr: the job passed by value, for njobs right-hand sides (sample s reads x + s * in and writes
-// y + s * out; workgroups [s * nblocks, (s + 1) * nblocks) serve it); else block b belongs to the last job of
-// the table whose block_start <= b
-template <int KA, int KB>
+// jobs == nullptr: the job passed by value, for njobs right-hand sides in groups of NB that share one pass
+// over the planes (group g reads x + g * NB * in and writes y + g * NB * out; workgroups [g * nblocks,
+// (g + 1) * nblocks) serve it); else (NB = 1) block b belongs to the last job of the table whose
+// block_start <= b
+template <int KA, int KB, int NB>
 __global__ void __launch_bounds__(64) gemv_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
   __shared__ __attribute__((aligned(16))) char lds[lds_bytes<KA, KB>()];
   if (jobs == nullptr) {
-    const int sample = blockIdx.x / one.nblocks;
-    one.x += (size_t)sample * one.ncw * 32;
-    one.y += (size_t)sample * one.out;
-    gemv_block<KA, KB>(one, blockIdx.x - sample * one.nblocks, threadIdx.x, lds);
+    const int group = blockIdx.x / one.nblocks;
+    one.x += (size_t)group * NB * one.ncw * 32;
+    one.y += (size_t)group * NB * one.out;
+    one.nsamples = min(NB, njobs - group * NB);
+    gemv_block<KA, KB, NB>(one, blockIdx.x - group * one.nblocks, threadIdx.x, lds);
     return;
   }
-  const int b = blockIdx.x;
-  int lo = 0, hi = njobs - 1;
-  while (lo < hi) {
-    int mid = (lo + hi + 1) >> 1;
-    if (jobs[mid].block_start <= b) lo = mid; else hi = mid - 1;
+  if constexpr (NB == 1) {
+    const int b = blockIdx.x;
+    int lo = 0, hi = njobs - 1;
+    while (lo < hi) {
+      int mid = (lo + hi + 1) >> 1;
+      if (jobs[mid].block_start <= b) lo = mid; else hi = mid - 1;
+    }
+    GemvJob job = jobs[lo];
+    gemv_block<KA, KB, 1>(job, b - job.block_start, threadIdx.x, lds);
   }
-  GemvJob job = jobs[lo];
-  gemv_block<KA, KB>(job, b - job.block_start, threadIdx.x, lds);
 }
 
 }  // namespace dpllm

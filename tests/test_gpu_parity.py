@@ -124,17 +124,27 @@ def test_gemv_llama7b_shapes_k3_to_8(dp, out, in_):
     model.close()
 
 
-@pytest.mark.parametrize("B", [2, 3, 4, 8])
+@pytest.mark.parametrize("B", [2, 3, 4, 5, 7, 8])
 def test_gemv_small_batch(dp, B):
-    lin = synth.make_linear(260, 4096, 8, 3, seed=B)
+    """Groups of two or four samples share one pass over the planes; ragged last group, ragged last strip."""
+    in_ = 4096 + 96
+    lin = synth.make_linear(260, in_, 8, 3, seed=B)
     model = load(dp, [lin])
-    X = synth.make_x(4096, B, seed=10 + B)
+    X = synth.make_x(in_, B, seed=10 + B)
     planes = synth.planes_np(lin["planes"])
-    for k in (3, 4, 5, 6):
+    for k in range(3, 9):
         ref = oracle.gemv(planes, k, synth.lut_np(lin["luts"][k]), synth.lut_np(X))
         got = model.dpllm_gemv(0, k, X.cuda()).float().cpu().numpy()
         assert got.shape == (B, 260)
-        assert rel_l2(got, ref) <= REL_L2
+        for b in range(B):
+            assert rel_l2(got[b], ref[b]) <= REL_L2, (k, b)
+    # bitwidth of a candidate pair read on the device, whole batch at that bitwidth
+    model.dpllm_set_selector(0, 4, 5, dp.DPLLM_SEL_LINREG, alpha=0.0, beta=1.0, T=0.5)
+    for k_sel in (4, 5):
+        k_dev = torch.tensor([k_sel], dtype=torch.int32, device="cuda")
+        got = model.dpllm_gemv(0, -1, X.cuda(), k_dev=k_dev).float().cpu().numpy()
+        ref = oracle.gemv(planes, k_sel, synth.lut_np(lin["luts"][k_sel]), synth.lut_np(X))
+        assert rel_l2(got, ref) <= REL_L2, k_sel
     model.close()
 
 
