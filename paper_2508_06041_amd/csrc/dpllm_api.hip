@@ -54,7 +54,8 @@ struct GemvLaunch {
   int blocks;
 };
 struct Phase {
-  int sel_first, sel_count, sel_blocks;
+  int sel_first, sel_count;     // slice of the device selector job table
+  int part_first, part_count;   // slice of the device selector part table
   std::vector<GemvLaunch> gemv;
 };
 struct StepPlan {
@@ -78,6 +79,10 @@ struct dpllm_model {
   // decode-step plan and its device tables
   StepPlan plan;
   SelJob* d_sel_jobs = nullptr;
+  SelPart* d_sel_parts = nullptr;
+  size_t sel_parts_cap = 0;
+  double* d_sel_ws = nullptr;       // one slot per selector part of the plan
+  double* d_sel_ws_one = nullptr;   // kSelMaxParts slots for dpllm_estimate
   GemvJob* d_gemv_jobs = nullptr;
   int device = 0;
 };
@@ -130,6 +135,8 @@ SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* 
   j.T = s.T; j.alpha = s.alpha; j.beta = s.beta;
   j.in = lin.L.in; j.r = s.r;
   j.l = s.l; j.h = s.h; j.kind = s.kind;
+  j.nparts = sel_parts_of(s.kind, s.r);
+  j.ws = nullptr;
   return j;
 }
 
@@ -258,6 +265,9 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     HIP_TRY(m, hipMalloc((void**)&m->d_gemv_jobs, sizeof(GemvJob) * n));
   }
   std::vector<SelJob> sel_jobs;
+  std::vector<SelPart> sel_parts;
+  std::vector<size_t> ws_offset;
+  size_t ws_slots = 0;
   int id = 0;
   while (id < n) {
     int end = id + 1;
@@ -275,14 +285,17 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     Phase ph;
     ph.sel_first = (int)sel_jobs.size();
     ph.sel_count = end - id;
-    int sb = 0;
+    ph.part_first = (int)sel_parts.size();
     for (int j = id; j < end; ++j) {
       const Linear& lin = m->linears[j];
       const Selector& s = lin.sel[lin.active];
-      sel_jobs.push_back(make_sel_job(lin, s, xs[j], e_dev + j, k_dev + j));
-      sb += 1;
+      SelJob sj = make_sel_job(lin, s, xs[j], e_dev + j, k_dev + j);
+      for (int part = 0; part < sj.nparts; ++part) sel_parts.push_back(SelPart{j - id, part});
+      ws_offset.push_back(ws_slots);
+      ws_slots += (size_t)sj.nparts;
+      sel_jobs.push_back(sj);
     }
-    ph.sel_blocks = sb;
+    ph.part_count = (int)sel_parts.size() - ph.part_first;
     // GEMV jobs of the phase, grouped by kernel instance in order of first appearance
     std::vector<std::pair<int, int>> classes;
     for (int j = id; j < end; ++j) {
@@ -323,6 +336,17 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   }
   // The tables may still be read by a step enqueued earlier: drain the stream before replacing them.
   HIP_TRY(m, hipStreamSynchronize(st));
+  if (sel_parts.size() > m->sel_parts_cap) {
+    if (m->d_sel_parts) (void)hipFree(m->d_sel_parts);
+    if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
+    m->d_sel_parts = nullptr; m->d_sel_ws = nullptr; m->sel_parts_cap = 0;
+    HIP_TRY(m, hipMalloc((void**)&m->d_sel_parts, sizeof(SelPart) * sel_parts.size()));
+    HIP_TRY(m, hipMalloc((void**)&m->d_sel_ws, sizeof(double) * sel_parts.size()));
+    m->sel_parts_cap = sel_parts.size();
+  }
+  for (size_t i = 0; i < sel_jobs.size(); ++i) sel_jobs[i].ws = m->d_sel_ws ? m->d_sel_ws + ws_offset[i] : nullptr;
+  if (!sel_parts.empty())
+    HIP_TRY(m, hipMemcpy(m->d_sel_parts, sel_parts.data(), sizeof(SelPart) * sel_parts.size(), hipMemcpyHostToDevice));
   HIP_TRY(m, hipMemcpy(m->d_sel_jobs, sel_jobs.data(), sizeof(SelJob) * sel_jobs.size(), hipMemcpyHostToDevice));
   HIP_TRY(m, hipMemcpy(m->d_gemv_jobs, P.gemv_jobs.data(), sizeof(GemvJob) * P.gemv_jobs.size(),
                        hipMemcpyHostToDevice));
@@ -333,6 +357,9 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
 
 void free_device(dpllm_model* m) {
   if (m->d_sel_jobs) (void)hipFree(m->d_sel_jobs);
+  if (m->d_sel_parts) (void)hipFree(m->d_sel_parts);
+  if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
+  if (m->d_sel_ws_one) (void)hipFree(m->d_sel_ws_one);
   if (m->d_gemv_jobs) (void)hipFree(m->d_gemv_jobs);
 }
 
@@ -496,7 +523,13 @@ int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, floa
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
   SelJob j = make_sel_job(*lin, lin->sel[slot], x_dev, e_dev, k_dev);
-  hipLaunchKernelGGL(selector_kernel, dim3(1), dim3(kSelThreads), 0, (hipStream_t)stream, (const SelJob*)nullptr, j);
+  if (!m->d_sel_ws_one) HIP_TRY(m, hipMalloc((void**)&m->d_sel_ws_one, sizeof(double) * kSelMaxParts));
+  j.ws = m->d_sel_ws_one;
+  if (j.nparts > 0)
+    hipLaunchKernelGGL(selector_part_kernel, dim3(j.nparts), dim3(kSelPartThreads), 0, (hipStream_t)stream,
+                       (const SelJob*)nullptr, (const SelPart*)nullptr, j);
+  hipLaunchKernelGGL(selector_decide_kernel, dim3(1), dim3(kSelDecideThreads), 0, (hipStream_t)stream,
+                     (const SelJob*)nullptr, 1, j);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -543,9 +576,14 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
   SelJob none{};
   GemvJob gnone{};
   for (const Phase& ph : P.phases) {
-    if (parts & DPLLM_STEP_SELECT)
-      hipLaunchKernelGGL(selector_kernel, dim3(ph.sel_blocks), dim3(kSelThreads), 0, st,
-                         (const SelJob*)(m->d_sel_jobs + ph.sel_first), none);
+    if (parts & DPLLM_STEP_SELECT) {
+      const SelJob* jobs = m->d_sel_jobs + ph.sel_first;
+      if (ph.part_count > 0)
+        hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
+                           (const SelPart*)(m->d_sel_parts + ph.part_first), none);
+      hipLaunchKernelGGL(selector_decide_kernel, dim3((ph.sel_count + kSelDecideThreads - 1) / kSelDecideThreads),
+                         dim3(kSelDecideThreads), 0, st, jobs, ph.sel_count, none);
+    }
     if (!(parts & DPLLM_STEP_GEMV)) continue;
     for (const GemvLaunch& gl : ph.gemv) {
       if (gl.ka != 0) {

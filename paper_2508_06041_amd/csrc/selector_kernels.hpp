@@ -1,11 +1,13 @@
-// Precision selector kernel (paper Sec. 3: the layer takes h when the relative error exceeds its threshold
+// Precision selector kernels (paper Sec. 3: the layer takes h when the relative error exceeds its threshold
 // T, else l; Sec. 5.1: the error is estimated as ||G x|| with G = A (W_h - W_l) precomputed, or as
-// alpha ||x|| + beta).  One launch serves a list of selector jobs, one workgroup (one compute unit) per
-// job; the bitwidth lands in device memory, where the GEMV kernels read it.
+// alpha ||x|| + beta).  One pair of launches serves a list of selector jobs; the bitwidth lands in device
+// memory, where the GEMV kernels read it.
 //
-// A job reads 0.5 - 3.5 MB of G; a workgroup of 16 wavefronts keeps enough loads in flight to pull that
-// through one compute unit in about ten microseconds, and a decode step has about as many jobs as the chip
-// has compute units, so no cross-workgroup reduction (atomics, fences, a second pass) is needed.
+// A job reads 0.5 - 3.5 MB of G.  It is cut into parts of 16 rows of G (one workgroup of four wavefronts,
+// four rows per wavefront sharing the activation loads); a part writes the fp64 sum of its g_j^2 to a
+// workspace slot of its own.  A second, tiny kernel adds the slots of every job in index order, takes the
+// square root and the decision.  No atomics and no fences: the order of all additions is fixed, and the
+// parts of long jobs spread over the whole chip instead of occupying one compute unit each.
 //
 // The estimate and the compare are taken in fp64: fp16 x fp16 products are exact in fp32, their sum runs in
 // fp64 in a fixed order, so a decision is reproducible and differs from an ideal-arithmetic decision only
@@ -18,19 +20,33 @@
 
 namespace dpllm {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kSelRowsPerPass = 4;   // rows of G a wavefront carries at once (they share the activation loads)
+constexpr int kSelPartThreads = 256;
+constexpr int kSelPartWaves = kSelPartThreads / 64;
+constexpr int kSelRowsPerWave = 4;   // rows of G a wavefront carries at once (they share the activation loads)
+constexpr int kSelDepth = 2;         // column tiles in registers: one being accumulated, one in flight
+constexpr int kSelPartRows = kSelPartWaves * kSelRowsPerWave;
 constexpr int kSelMaxRank = 1024;
+constexpr int kSelMaxParts = kSelMaxRank / kSelPartRows;
+constexpr int kSelDecideThreads = 256;
 
 struct SelJob {
   const uint16_t* G;   // fp16 [r][in] (projection kind)
   const uint16_t* x;   // fp16 [in]
   float* e_out;
   int32_t* k_out;
+  double* ws;          // nparts workspace slots of this job
   float T, alpha, beta;
   int32_t in, r, l, h, kind;  // kind: 0 none, 1 projection, 2 linear regression
+  int32_t nparts;             // projection: ceil(r / 16); linear regression: 1; none: 0
 };
+struct SelPart {
+  int32_t job;    // index into the job table of the launch
+  int32_t part;   // part number inside the job: rows [16 part, 16 part + 16)
+};
+
+__host__ __device__ inline int sel_parts_of(int kind, int r) {
+  return kind == 1 ? (r + kSelPartRows - 1) / kSelPartRows : (kind == 2 ? 1 : 0);
+}
 
 __device__ __forceinline__ double wave_sum_f64(double v) {
 #pragma unroll
@@ -38,28 +54,46 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
   return v;
 }
 
-__device__ __forceinline__ void publish_decision(double e, float T, int l, int h, float* e_out, int32_t* k_out) {
-  *e_out = (float)e;
-  *k_out = (e > (double)T) ? h : l;  // strictly exceeding T selects h; +inf pins l, -inf pins h
-}
+typedef uint32_t sel_u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ void accumulate8(const uint4& gv, const float (&xf)[8], double& acc) {
-  const __half* gh = reinterpret_cast<const __half*>(&gv);
+struct SelTile {
+  sel_u32x4 g[kSelRowsPerWave];
+  uint4 x;
+};
+
+// columns [c, c + 8) of the wavefront's four rows and of x; c is clamped by the caller, so the loads are
+// unconditional and the next tile can be in flight while the current one is accumulated
+// (pointers taken from a job record are generic; global-address-space loads keep them on the vector-memory path)
+#define DPLLM_SEL_GLOBAL __attribute__((address_space(1)))
+__device__ __forceinline__ void sel_load(SelTile& t, const uint16_t* const (&rows)[kSelRowsPerWave], const uint16_t* x, int c) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) acc += (double)(__half2float(gh[i]) * xf[i]);  // product exact in fp32
+  for (int i = 0; i < kSelRowsPerWave; ++i)
+    t.g[i] = __builtin_nontemporal_load((const DPLLM_SEL_GLOBAL sel_u32x4*)(rows[i] + c));
+  const sel_u32x4 xv = *(const DPLLM_SEL_GLOBAL sel_u32x4*)(x + c);
+  t.x = make_uint4(xv.x, xv.y, xv.z, xv.w);
 }
 
-__device__ __forceinline__ void selector_block(const SelJob& job, int tid) {
-  __shared__ double g[kSelMaxRank];
-  __shared__ double red[kSelWaves];
-  const int wave = tid >> 6, lane = tid & 63;
-  if (job.kind == 0) {
-    if (tid == 0) { *job.e_out = 0.f; *job.k_out = job.l; }
-    return;
+__device__ __forceinline__ void sel_accumulate(const SelTile& t, bool valid, double (&acc)[kSelRowsPerWave]) {
+  const __half* xh = reinterpret_cast<const __half*>(&t.x);
+  double xd[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) xd[i] = valid ? (double)__half2float(xh[i]) : 0.0;
+#pragma unroll
+  for (int r = 0; r < kSelRowsPerWave; ++r) {
+    const __half* gh = reinterpret_cast<const __half*>(&t.g[r]);
+    // an fp16 x fp16 product is exact in fp64, so the fused multiply-add rounds once, like an fp64 add of the
+    // exact product
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[r] = fma((double)__half2float(gh[i]), xd[i], acc[r]);
   }
-  if (job.kind == 2) {
+}
+
+__device__ __forceinline__ void selector_part(const SelJob& job, int part, int tid) {
+  __shared__ double red[kSelPartRows];
+  const int wave = tid >> 6, lane = tid & 63;
+  if (job.kind == 2) {   // sum of x^2, one part
     double acc = 0.0;
-    for (int c = tid * 8; c < job.in; c += kSelThreads * 8) {
+    for (int c = tid * 8; c < job.in; c += kSelPartThreads * 8) {
       uint4 xv = *reinterpret_cast<const uint4*>(job.x + c);
       const __half* xh = reinterpret_cast<const __half*>(&xv);
 #pragma unroll
@@ -73,59 +107,89 @@ __device__ __forceinline__ void selector_block(const SelJob& job, int tid) {
     __syncthreads();
     if (tid == 0) {
       double tot = 0.0;
-      for (int w = 0; w < kSelWaves; ++w) tot += red[w];
-      publish_decision((double)job.alpha * sqrt(tot) + (double)job.beta, job.T, job.l, job.h, job.e_out, job.k_out);
+      for (int w = 0; w < kSelPartWaves; ++w) tot += red[w];
+      job.ws[0] = tot;
     }
     return;
   }
-  // projection: wavefront w owns rows w, w + 16, ...; four of them per pass over the columns
-  for (int j0 = wave; j0 < job.r; j0 += kSelWaves * kSelRowsPerPass) {
-    const uint16_t* rows[kSelRowsPerPass];
+  // projection: wavefront w owns rows 16 part + 4 w .. + 3 (clamped to r - 1; surplus rows are dropped)
+  const int row0 = part * kSelPartRows + wave * kSelRowsPerWave;
+  const uint16_t* rows[kSelRowsPerWave];
 #pragma unroll
-    for (int i = 0; i < kSelRowsPerPass; ++i)
-      rows[i] = job.G + (size_t)min(j0 + i * kSelWaves, job.r - 1) * job.in;
-    double acc[kSelRowsPerPass];
+  for (int i = 0; i < kSelRowsPerWave; ++i) rows[i] = job.G + (size_t)min(row0 + i, job.r - 1) * job.in;
+  double acc[kSelRowsPerWave];
 #pragma unroll
-    for (int i = 0; i < kSelRowsPerPass; ++i) acc[i] = 0.0;
-    for (int c = lane * 8; c < job.in; c += 64 * 8) {
-      uint4 xv = *reinterpret_cast<const uint4*>(job.x + c);
-      typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-      uint4 gv[kSelRowsPerPass];
+  for (int i = 0; i < kSelRowsPerWave; ++i) acc[i] = 0.0;
+  const int last = job.in - 8;          // in % 32 == 0, so every 8-column group is whole
+  const int nit = (job.in + 511) / 512;
+  // Rows of G are a power-of-two number of bytes apart in the common shapes, so wavefronts that all walk the
+  // columns from 0 would hit the same few memory channels at any moment: every wavefront starts its
+  // (circular) walk at a different 1 KiB column chunk.
+  int it = (int)((blockIdx.x * kSelPartWaves + wave) * 5u % (unsigned)nit);   // tile being loaded
+  int ca = it * 512 + lane * 8;                                               // first column of the tile being accumulated
+  SelTile ring[kSelDepth];
 #pragma unroll
-      for (int i = 0; i < kSelRowsPerPass; ++i) {
-        u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(rows[i] + c));
-        gv[i] = make_uint4(t.x, t.y, t.z, t.w);
-      }
-      const __half* xh = reinterpret_cast<const __half*>(&xv);
-      float xf[8];
+  for (int d = 0; d < kSelDepth - 1; ++d) {
+    sel_load(ring[d], rows, job.x, min(it * 512 + lane * 8, last));
+    it = it + 1 == nit ? 0 : it + 1;
+  }
+  for (int k = 0; k < nit; k += kSelDepth) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) xf[i] = __half2float(xh[i]);
-#pragma unroll
-      for (int i = 0; i < kSelRowsPerPass; ++i) accumulate8(gv[i], xf, acc[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < kSelRowsPerPass; ++i) {
-      double v = wave_sum_f64(acc[i]);
-      int j = j0 + i * kSelWaves;
-      if (lane == 0 && j < job.r) g[j] = v;
+    for (int d = 0; d < kSelDepth; ++d) {
+      // loads past the end of the walk re-read a tile that is never accumulated (uniform, unconditional issue)
+      sel_load(ring[(d + kSelDepth - 1) % kSelDepth], rows, job.x, min(it * 512 + lane * 8, last));
+      it = it + 1 == nit ? 0 : it + 1;
+      if (k + d < nit) sel_accumulate(ring[d], ca <= last, acc);
+      ca = ca + 512 >= nit * 512 ? ca + 512 - nit * 512 : ca + 512;
     }
   }
+#pragma unroll
+  for (int i = 0; i < kSelRowsPerWave; ++i) {
+    double v = wave_sum_f64(acc[i]);
+    if (lane == 0) red[wave * kSelRowsPerWave + i] = (row0 + i < job.r) ? v * v : 0.0;
+  }
   __syncthreads();
-  if (wave == 0) {
+  if (tid == 0) {
     double sq = 0.0;
-    for (int j = lane; j < job.r; j += 64) sq += g[j] * g[j];
-    sq = wave_sum_f64(sq);
-    if (lane == 0) publish_decision(sqrt(sq), job.T, job.l, job.h, job.e_out, job.k_out);
+    for (int j = 0; j < kSelPartRows; ++j) sq += red[j];
+    job.ws[part] = sq;
   }
 }
 
-// jobs == nullptr: the single job passed by value; else workgroup b serves jobs[b]
-__global__ void __launch_bounds__(kSelThreads) selector_kernel(const SelJob* __restrict__ jobs, SelJob one) {
-  if (jobs == nullptr) {
-    selector_block(one, threadIdx.x);
+// parts == nullptr: the single job passed by value, workgroup b is its part b; else workgroup b serves parts[b]
+__global__ void __launch_bounds__(kSelPartThreads) selector_part_kernel(const SelJob* __restrict__ jobs,
+                                                                         const SelPart* __restrict__ parts, SelJob one) {
+  if (parts == nullptr) {
+    selector_part(one, blockIdx.x, threadIdx.x);
   } else {
-    SelJob job = jobs[blockIdx.x];
-    selector_block(job, threadIdx.x);
+    const SelPart p = parts[blockIdx.x];
+    SelJob job = jobs[p.job];
+    selector_part(job, p.part, threadIdx.x);
+  }
+}
+
+__device__ __forceinline__ void selector_decide(const SelJob& job) {
+  double tot = 0.0;
+  for (int i = 0; i < job.nparts; ++i) tot += job.ws[i];
+  double e = 0.0;
+  if (job.kind == 1) e = sqrt(tot);
+  else if (job.kind == 2) e = (double)job.alpha * sqrt(tot) + (double)job.beta;
+  *job.e_out = (float)e;
+  // strictly exceeding T selects h; +inf pins l, -inf pins h; no estimator: always l
+  *job.k_out = (job.kind != 0 && e > (double)job.T) ? job.h : job.l;
+}
+
+// one thread per job; jobs == nullptr: the single job passed by value
+__global__ void __launch_bounds__(kSelDecideThreads) selector_decide_kernel(const SelJob* __restrict__ jobs, int njobs,
+                                                                             SelJob one) {
+  if (jobs == nullptr) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) selector_decide(one);
+    return;
+  }
+  const int j = blockIdx.x * kSelDecideThreads + threadIdx.x;
+  if (j < njobs) {
+    SelJob job = jobs[j];
+    selector_decide(job);
   }
 }
 
