@@ -48,6 +48,13 @@ struct GemvJob {
 
 __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
 
+// v_bfi_b32 with a wavefront-uniform mask (held in a scalar register)
+__device__ __forceinline__ uint32_t bfi_insn(uint32_t mask, uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "s"(mask), "v"(a), "v"(b));
+  return r;
+}
+
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_add(float v) {
   int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false);
@@ -132,7 +139,9 @@ __device__ __forceinline__ void merge_pair_fields(const uint32_t (&w)[3], uint32
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj) {
     const uint32_t m0 = rotl_c(0x90909090u, 2 * jj), m1 = rotl_c(0x48484848u, 2 * jj), m2 = rotl_c(0x24242424u, 2 * jj);
-    uint32_t o = (w[0] & m0) | (w[1] & m1) | (w[2] & m2);
+    // three instructions per word; written as instructions because the compiler rewrites the expression into
+    // three ANDs and a three-way OR
+    uint32_t o = bfi_insn(m0, w[0], bfi_insn(m1, w[1], w[2] & m2));
     T[jj] = jj ? __builtin_rotateright32(o, 2 * jj) : o;
   }
 }
@@ -275,15 +284,16 @@ template <int K>
 __device__ __forceinline__ void consume_chunk(const uint32_t (&v)[8], const uint32_t* xp4, const float (&xf)[8],
                                               float& acc0, float& acc1) {
   using D = Decode<K>;
+  // last lookup first: LDS answers in issue order, so one counter wait covers the chunk
 #pragma unroll
-  for (int n = 0; n < 4; ++n) {
+  for (int n = 3; n >= 0; --n) {
     if constexpr (D::scheme == Scheme::kF32) {
-      acc0 = __builtin_fmaf(__builtin_bit_cast(float, v[2 * n]), xf[2 * n], acc0);
       acc1 = __builtin_fmaf(__builtin_bit_cast(float, v[2 * n + 1]), xf[2 * n + 1], acc1);
+      acc0 = __builtin_fmaf(__builtin_bit_cast(float, v[2 * n]), xf[2 * n], acc0);
     } else {
       half2_t xv = __builtin_bit_cast(half2_t, xp4[n]);
-      acc0 = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)v[2 * n]), (float)xv.x, acc0);
       acc1 = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)v[2 * n + 1]), (float)xv.y, acc1);
+      acc0 = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)v[2 * n]), (float)xv.x, acc0);
     }
   }
 }
@@ -297,7 +307,6 @@ __device__ __forceinline__ void byte_pipeline(const uint32_t (&R)[2][8], const u
     if constexpr (C + 1 < 8)
       issue_chunk<K, (C + 1) / 2>(R[(C + 1) % 2], lds + (2 * H + (C + 1) % 2) * Decode<K>::row_bytes, vb);
     sched_fence();
-    if constexpr (C + 1 < 8) wait_lds<8>(); else wait_lds<0>();
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       if constexpr (Decode<K>::scheme == Scheme::kF32 && rr == 0) {
@@ -362,13 +371,13 @@ __device__ __forceinline__ void pair_pipeline(const uint32_t (&T)[4][4], const u
     constexpr int jj = C / 2, r0 = 2 * (C % 2);
     if constexpr (C + 1 < 8) issue_pair_chunk<K, C + 1>(T, lds, vb);
     sched_fence();
-    if constexpr (C + 1 < 8) wait_lds<8>(); else wait_lds<0>();
+    // LDS answers in issue order: consuming the chunk's last lookup first lets one counter wait cover all eight
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int rr = 0; rr < 2; ++rr)
+      for (int rr = 1; rr >= 0; --rr)
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {
+        for (int n = 3; n >= 0; --n) {
           float& a = acc[b][2 * (r0 + rr) + (n & 1)];
           a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, va[4 * rr + n]), __builtin_bit_cast(half2_t, xp[b][4 * jj + n]), a, false);
         }
