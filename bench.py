@@ -114,6 +114,8 @@ def main():
     xbuf = {in_: torch.empty(in_, dtype=torch.float16, device="cuda") for in_ in ins}
     xs = [xbuf[in_] for _, in_ in meta["shapes"]]
     ys = [torch.empty(out, dtype=torch.float16, device="cuda") for out, _ in meta["shapes"]]
+    x_tensors, y_tensors = xs, ys                     # keep the tensors alive; the calls take pointer arrays
+    xs, ys = model.pointers(x_tensors), model.pointers(y_tensors)
     k_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
     e_dev = torch.zeros(n, dtype=torch.float32, device="cuda")
 

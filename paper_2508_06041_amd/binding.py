@@ -160,15 +160,21 @@ class Model:
         _check(self.h, lib.dpllm_gemv(self.h, id, k, _ptr(k_dev), _ptr(x), _ptr(y), B, _stream()))
         return y
 
+    def pointers(self, tensors):
+        """The host array of n_linears device pointers the step calls take; build it once for tensors that stay
+        where they are and pass it instead of the list (the caller keeps the tensors alive)."""
+        if isinstance(tensors, C.Array):
+            return tensors
+        assert len(tensors) == self.n
+        return (C.c_void_p * self.n)(*[t.data_ptr() for t in tensors])
+
     def dpllm_decode_step(self, xs, ys, k_out, e_out):
-        xa = (C.c_void_p * self.n)(*[t.data_ptr() for t in xs])
-        ya = (C.c_void_p * self.n)(*[t.data_ptr() for t in ys])
-        _check(self.h, lib.dpllm_decode_step(self.h, xa, ya, _ptr(k_out), _ptr(e_out), _stream()))
+        _check(self.h, lib.dpllm_decode_step(self.h, self.pointers(xs), self.pointers(ys), _ptr(k_out), _ptr(e_out),
+                                             _stream()))
 
     def dpllm_decode_step_parts(self, xs, ys, k_out, e_out, parts):
-        xa = (C.c_void_p * self.n)(*[t.data_ptr() for t in xs])
-        ya = (C.c_void_p * self.n)(*[t.data_ptr() for t in ys])
-        _check(self.h, lib.dpllm_decode_step_parts(self.h, xa, ya, _ptr(k_out), _ptr(e_out), parts, _stream()))
+        _check(self.h, lib.dpllm_decode_step_parts(self.h, self.pointers(xs), self.pointers(ys), _ptr(k_out),
+                                                   _ptr(e_out), parts, _stream()))
 
     def dpllm_debug_unpack(self, id, k):
         out, in_, _, _ = self.shapes.get(id, (1, 32, 0, 0))
