@@ -150,6 +150,11 @@ int dpllm_debug_unpack(dpllm_model* m, int id, int k, uint8_t* idx_dev, void* st
  * profiles report for the GEMV.  Errors: EINVAL, EHIP. */
 int dpllm_debug_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
 
+/* Measurement aid: a plain 128-bit non-temporal streaming read of `bytes` (bytes % 16 == 0, pointers device and
+ * 16-byte aligned; sink_dev: 16 writable bytes, practically never written).  Its rate over >= 1 GiB is the
+ * measured HBM read ceiling the GEMV's rate is reported against.  Errors: EINVAL, EHIP. */
+int dpllm_debug_read(const void* src_dev, size_t bytes, void* sink_dev, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,7 @@ DPLLM_STEP_SELECT, DPLLM_STEP_GEMV = 1, 2
 
 SYMBOLS = ["dpllm_model_create", "dpllm_model_destroy", "dpllm_last_error", "dpllm_linear_device_bytes",
            "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair",
-           "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_copy"]
+           "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_copy", "dpllm_debug_read"]
 
 
 class DpllmError(RuntimeError):
@@ -49,6 +49,7 @@ def _load():
     L.dpllm_decode_step_parts.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, i32, vp]
     L.dpllm_debug_unpack.argtypes = [vp, i32, i32, vp, vp]
     L.dpllm_debug_copy.argtypes = [vp, vp, sz, vp]
+    L.dpllm_debug_read.argtypes = [vp, sz, vp, vp]
     return L
 
 
@@ -84,6 +85,13 @@ def dpllm_debug_copy(dst, src):
     rc = lib.dpllm_debug_copy(_ptr(dst), _ptr(src), nbytes, _stream())
     if rc != 0:
         raise DpllmError(rc, "dpllm_debug_copy")
+
+
+def dpllm_debug_read(src, sink):
+    nbytes = src.numel() * src.element_size()
+    rc = lib.dpllm_debug_read(_ptr(src), nbytes, _ptr(sink), _stream())
+    if rc != 0:
+        raise DpllmError(rc, "dpllm_debug_read")
 
 
 class Model:
