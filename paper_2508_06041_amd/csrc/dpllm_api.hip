@@ -628,7 +628,7 @@ int dpllm_debug_copy(void* dst_dev, const void* src_dev, size_t bytes, void* str
 
 int dpllm_debug_read(const void* src_dev, size_t bytes, void* sink_dev, void* stream) {
   if (!src_dev || !sink_dev || bytes % 16 || ((uintptr_t)src_dev | (uintptr_t)sink_dev) % 16) return DPLLM_EINVAL;
-  hipLaunchKernelGGL(plain_read_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src_dev,
+  hipLaunchKernelGGL(plain_read_kernel, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (const uint4*)src_dev,
                      bytes / 16, (uint4*)sink_dev);
   return hipGetLastError() == hipSuccess ? DPLLM_OK : DPLLM_EHIP;
 }

@@ -672,7 +672,10 @@ __device__ __forceinline__ void gemv_block(const GemvJob& job, int block, int la
 // block_start <= b
 template <int KA, int KB, int NB>
 __global__ void __launch_bounds__(64) gemv_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
-  __shared__ __attribute__((aligned(16))) char lds[lds_bytes<KA, KB>()];
+#ifndef DPLLM_LDS_PAD
+#define DPLLM_LDS_PAD 0
+#endif
+  __shared__ __attribute__((aligned(16))) char lds[lds_bytes<KA, KB>() + DPLLM_LDS_PAD];
   if (jobs == nullptr) {
     const int group = blockIdx.x / one.nblocks;
     one.x += (size_t)group * NB * one.ncw * 32;
