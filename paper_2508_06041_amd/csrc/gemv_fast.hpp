@@ -1,23 +1,25 @@
-// Any-precision GEMV for gfx950, batch 1: y[o] = sum_c LUT_k[o][code_k(o,c)] * x[c]   (paper Sec. 3: the
-// linear operation of a decode step; Sec. 2.2: the k-bit model is the top k planes of the parent).
+// Any-precision GEMV for gfx950: y[o] = sum_c LUT_k[o][code_k(o,c)] * x[c]   (paper Sec. 3: the linear
+// operation of a decode step; Sec. 2.2: the k-bit model is the top k planes of the parent), for one right-hand
+// side or a small group of them.
 //
-// Work split: one 64-lane wavefront (= one workgroup) owns a run of consecutive row quads and streams
-// them strip by strip (strip = 4 rows x 64 words of 32 columns).  A lane loads one 128-bit value per plane
-// and strip, so a wavefront load is 1 KiB of contiguous memory per plane; only planes 0..k-1 are read.  The
-// loads of strip t+1 (also across row-quad boundaries) are in flight while strip t is decoded, which keeps
-// HBM busy during the ALU-heavy decode.
+// Work split: one 64-lane wavefront (= one workgroup) streams row quads b, b + nblocks, ... strip by strip
+// (strip = 4 rows x 64 words of 32 columns).  A lane loads one 128-bit value per plane and strip, so a wavefront
+// load is 1 KiB of contiguous memory per plane; only planes 0..k-1 are read.  The loads of strip t+1 (also
+// across row-quad boundaries) are in flight while strip t is decoded.
 //
 // Decoding: the layout keeps the k bits of a weight at adjacent descending positions of planes 0..k-1
 // (see layout_device.hpp), so code fields are built by mask-merging whole plane words (v_bfi_b32), never
 // bit by bit:
-//   k = 3   : three merges give a word of four bytes [a2 a1 a0 b2 b1 b0 0 0]: the byte is the LDS offset
+//   k = 3   : three instructions per word give four bytes [a2 a1 a0 b2 b1 b0 0 0]: the byte is the LDS offset
 //             of entry (a,b) of a per-row table of fp16 pairs (64 entries); one LDS read returns both
 //             weights packed, one v_dot2_f32_f16 multiplies them with the packed activations (2i, 2i+1).
-//   k != 3  : a three-level merge tree (2-, 4-, 8-bit fields) gives eight words of four bytes [code << 1]
-//             (k = 8: [code]); the byte is the LDS offset into the row's fp16 table; one fp32 mixed FMA
-//             per weight.
-// The per-row tables sit in LDS (wavefront-private: 64 B..2 KiB); activations are read from global memory
-// (L1/L2 hits) straight into packed registers, because LDS lookups are the scarcest resource at low k.
+//   k = 4   : the 4-bit code words are bytes 16 a + b of two weights four positions apart; a 256-entry pair
+//             table per row is built in LDS from the row's 16 centroids; activations are re-paired to match.
+//   k >= 5  : a three-level merge tree (2-, 4-, 8-bit fields) gives eight words of four bytes [code << s];
+//             the byte is the LDS offset into the row's table (k = 5: fp32 entries, k >= 6: fp16 entries); one
+//             multiply-add per weight.
+// The per-row tables sit in LDS (wavefront-private: 1 KiB..4 KiB per row quad); activations are read from
+// global memory (L1/L2 hits) straight into packed registers, because LDS lookups are the scarcest resource.
 // All accumulation is fp32; the four row sums are reduced across the wavefront with DPP adds.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -197,11 +199,6 @@ __device__ __forceinline__ uint32_t byte_of(uint32_t w) {
 }
 
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
-
-// Waits until at most N LDS operations of this wavefront are outstanding (global loads are not waited for).
-// One wait per chunk of lookups replaces the descending per-use waits the compiler would insert.
-template <int N>
-__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8)); }
 
 template <int K>
 struct PlaneStrip {
@@ -672,10 +669,7 @@ __device__ __forceinline__ void gemv_block(const GemvJob& job, int block, int la
 // block_start <= b
 template <int KA, int KB, int NB>
 __global__ void __launch_bounds__(64) gemv_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
-#ifndef DPLLM_LDS_PAD
-#define DPLLM_LDS_PAD 0
-#endif
-  __shared__ __attribute__((aligned(16))) char lds[lds_bytes<KA, KB>() + DPLLM_LDS_PAD];
+  __shared__ __attribute__((aligned(16))) char lds[lds_bytes<KA, KB>()];
   if (jobs == nullptr) {
     const int group = blockIdx.x / one.nblocks;
     one.x += (size_t)group * NB * one.ncw * 32;

@@ -252,6 +252,93 @@ def test_decode_step_matches_oracle(dp, mode):
     model.close()
 
 
+
+def test_decode_step_chained_buffers_run_in_order(dp):
+    """Linears that read what earlier ones write (o <- v, gate/up <- o, down <- gate) are ordered by the
+    library: the result equals running them one after the other.  Bitwidths are pinned (alternating +/-inf) so
+    that the comparison does not hinge on estimates of slightly different inputs; the oracle chains its own
+    fp16-rounded outputs."""
+    shapes = [(128, 256), (128, 256), (256, 256), (256, 256), (320, 256), (320, 256), (256, 320)]
+    names = ["q", "k", "v", "o", "gate", "up", "down"]
+    src = {"q": None, "k": None, "v": None, "o": "v", "gate": "o", "up": "o", "down": "gate"}
+    lins, refs = [], []
+    model = dp.Model(len(shapes))
+    for i, (out, in_) in enumerate(shapes):
+        lin = synth.make_linear(out, in_, 5, 3, seed=4100 + i)
+        T = float("inf") if i % 2 == 0 else float("-inf")
+        G = synth.make_G(lin, 3, 4, 16, seed=4200 + i)
+        model.dpllm_load_linear(i, synth.planes_np(lin["planes"]),
+                                {k: synth.lut_np(v) for k, v in lin["luts"].items()}, 3)
+        model.dpllm_set_selector(i, 3, 4, dp.DPLLM_SEL_PROJ, G=G.cuda(), T=T)
+        refs.append({"planes": synth.planes_np(lin["planes"]),
+                     "luts": {k: synth.lut_np(v) for k, v in lin["luts"].items()},
+                     "selector": {"l": 3, "h": 4, "kind": 1, "G": synth.lut_np(G), "T": T}})
+    x0 = (synth.make_x(256, 1, seed=4300)[0].float() / 1024).half()   # keeps the chain inside fp16 range
+    ybuf = {nm: torch.zeros(out, dtype=torch.float16, device="cuda") for nm, (out, _) in zip(names, shapes)}
+    x0_dev = x0.cuda()
+    xs = [x0_dev if src[nm] is None else ybuf[src[nm]] for nm in names]
+    ys = [ybuf[nm] for nm in names]
+    k_dev = torch.zeros(len(shapes), dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(len(shapes), dtype=torch.float32, device="cuda")
+    for _ in range(2):     # second call: cached plan
+        for b in ybuf.values():
+            b.zero_()
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+        torch.cuda.synchronize()
+        ref_y = {}
+        for i, nm in enumerate(names):
+            x = synth.lut_np(x0) if src[nm] is None else ref_y[src[nm]].astype(np.float16).view(np.uint16)
+            k_ref = 3 if i % 2 == 0 else 4
+            ref_y[nm] = oracle.gemv(refs[i]["planes"], k_ref, refs[i]["luts"][k_ref], x)
+            assert int(k_dev[i]) == k_ref
+            assert rel_l2(ybuf[nm].float().cpu().numpy(), ref_y[nm]) <= REL_L2, nm
+    model.close()
+
+
+def test_decode_step_under_graph_capture_replays(dp):
+    """A step with a cached plan only enqueues kernels, so it can be captured in a graph; every replay, with
+    eager work and new inputs in between, must give what the eager call gives (bit for bit) and the oracle's
+    decisions."""
+    shapes = [(128, 256), (64, 256), (320, 256), (256, 320)]
+    n_steps = 5
+    model, refs, xs_by_in = _step_model(dp, shapes, 5, 3, 4, 64, n_steps, seed=5100, mode="mixed")
+    n = len(shapes)
+    xbuf = {in_: torch.zeros(in_, dtype=torch.float16, device="cuda") for in_ in xs_by_in}
+    xs = [xbuf[in_] for _, in_ in shapes]
+    ys = [torch.zeros(out, dtype=torch.float16, device="cuda") for out, _ in shapes]
+    k_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(n, dtype=torch.float32, device="cuda")
+
+    def set_inputs(t):
+        for in_ in xbuf:
+            xbuf[in_].copy_(xs_by_in[in_][t])
+
+    set_inputs(0)
+    model.dpllm_decode_step(xs, ys, k_dev, e_dev)      # builds the plan (not capturable: it copies tables)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+    for t in range(n_steps):
+        set_inputs(t)
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+        torch.cuda.synchronize()
+        eager_y = [y.clone() for y in ys]
+        eager_k, eager_e = k_dev.clone(), e_dev.clone()
+        for y in ys:
+            y.zero_()
+        k_dev.zero_()
+        e_dev.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        _, rk, _ = oracle.decode_step(refs, [synth.lut_np(xs_by_in[in_][t]) for _, in_ in shapes])
+        assert k_dev.cpu().numpy().tolist() == rk.tolist()
+        assert torch.equal(k_dev, eager_k) and torch.equal(e_dev, eager_e)
+        for y, ey in zip(ys, eager_y):
+            assert torch.equal(y, ey)
+    model.close()
+
+
 # ----------------------------------------------------------------------------- T7 error paths
 def test_abi_error_paths(dp):
     lin = synth.make_linear(8, 64, 4, 3, seed=1)
