@@ -101,6 +101,14 @@ int dpllm_set_threshold(dpllm_model* m, int id, int l, int h, float T);
 /* Chooses which of a linear's pairs dpllm_decode_step uses.  Errors: ESTATE. */
 int dpllm_set_active_pair(dpllm_model* m, int id, int l, int h);
 
+/* Asynchronous estimation (Sec. 5.2): the selector of a layer fed by the residual stream may read the
+ * previous residual vector instead of the layer's immediate input, which takes the estimate off the critical
+ * path.  xsel_dev (device fp16 [in], 16-byte aligned, borrowed) replaces the input of linear id's selector in
+ * dpllm_decode_step / dpllm_decode_step_parts; the GEMV still reads xs[id].  NULL restores the immediate
+ * input.  The step keeps sequential semantics: a selector input written by an earlier linear of the step is
+ * read after that linear has run.  Reloading the linear clears it.  Errors: EINVAL, ESTATE. */
+int dpllm_set_selector_input(dpllm_model* m, int id, const void* xsel_dev);
+
 /* "Estimate the relative error for (layer, x)" (Sec. 5.1) and select (Sec. 3):
  * e_dev[0] = estimate (fp32, rounded from the fp64 the decision is taken in),
  * k_dev[0] = h if estimate > T else l.  x_dev: device fp16 [in].  e_dev, k_dev: device.

@@ -155,8 +155,12 @@ def effective_bits(ks, params) -> float:
     return float(lib().orc_effective_bits(_p(ks), _p(params), ks.size))
 
 
-def decode_step(linears, xs):
+def decode_step(linears, xs, xs_sel=None):
     """Selector then GEMV for every linear in model order.
+
+    xs_sel: optional list; where an entry is not None the selector of that linear reads it instead of the
+            linear's input (paper Sec. 5.2, asynchronous estimation: layers fed by the residual stream may
+            estimate on the previous residual vector); the GEMV always reads xs.
 
     linears: list of dicts with planes, luts {k: lut}, and a selector dict
              {l, h, kind (0 none, 1 projection, 2 linear regression), G, alpha, beta, T}.
@@ -164,14 +168,15 @@ def decode_step(linears, xs):
     Returns (ys, ks, es).
     """
     ys, ks, es = [], [], []
-    for lin, x in zip(linears, xs):
+    for i, (lin, x) in enumerate(zip(linears, xs)):
         sel = lin["selector"]
         l, h = sel["l"], sel["h"]
+        xe = x if xs_sel is None or xs_sel[i] is None else xs_sel[i]
         if sel["kind"] == 1:
-            e = estimate(sel["G"], x)
+            e = estimate(sel["G"], xe)
             k = decide(e, sel["T"], l, h)
         elif sel["kind"] == 2:
-            e = linreg_estimate(x, sel["alpha"], sel["beta"])
+            e = linreg_estimate(xe, sel["alpha"], sel["beta"])
             k = decide(e, sel["T"], l, h)
         else:
             e, k = 0.0, l

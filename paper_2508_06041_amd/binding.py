@@ -17,7 +17,7 @@ DPLLM_MAX_BATCH = 8
 DPLLM_STEP_SELECT, DPLLM_STEP_GEMV = 1, 2
 
 SYMBOLS = ["dpllm_model_create", "dpllm_model_destroy", "dpllm_last_error", "dpllm_linear_device_bytes",
-           "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair",
+           "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair", "dpllm_set_selector_input",
            "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_copy", "dpllm_debug_read"]
 
 
@@ -43,6 +43,7 @@ def _load():
     L.dpllm_set_selector.argtypes = [vp, i32, i32, i32, i32, vp, i32, f32, f32, f32]
     L.dpllm_set_threshold.argtypes = [vp, i32, i32, i32, f32]
     L.dpllm_set_active_pair.argtypes = [vp, i32, i32, i32]
+    L.dpllm_set_selector_input.argtypes = [vp, i32, vp]
     L.dpllm_estimate.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
     L.dpllm_gemv.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp]
     L.dpllm_decode_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
@@ -107,6 +108,7 @@ class Model:
         self.arenas = {}
         self.keep = {}
         self.shapes = {}
+        self._sel_inputs = {}
 
     def close(self):
         if self.h:
@@ -152,6 +154,12 @@ class Model:
 
     def dpllm_set_active_pair(self, id, l, h):
         _check(self.h, lib.dpllm_set_active_pair(self.h, id, l, h))
+
+    def dpllm_set_selector_input(self, id, x_sel):
+        """x_sel: device fp16 [in] the selector of linear id reads in the step calls (None: its immediate input).
+        The model keeps a reference to the tensor."""
+        self._sel_inputs[id] = x_sel
+        _check(self.h, lib.dpllm_set_selector_input(self.h, id, _ptr(x_sel)))
 
     def dpllm_estimate(self, id, l, h, x, e_out=None, k_out=None):
         e_out = torch.empty(1, dtype=torch.float32, device="cuda") if e_out is None else e_out

@@ -35,6 +35,7 @@ struct Linear {
   char* arena = nullptr;
   Selector sel[DPLLM_MAX_PAIRS];
   int active = -1;
+  const void* sel_input = nullptr;   // decode step: the selector reads this vector instead of the linear's input
   const uint4* planes() const { return reinterpret_cast<const uint4*>(arena); }
   const uint16_t* lut(int k) const { return reinterpret_cast<const uint16_t*>(arena + L.lut_offset[k]); }
   int find_pair(int l, int h) const {
@@ -277,6 +278,8 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       for (int j = id; j < end && !dep; ++j) {
         const Linear& lj = m->linears[j];
         dep = overlap(xs[end], (size_t)le.L.in * 2, ys[j], (size_t)lj.L.out * 2) ||
+              (le.sel_input && overlap(le.sel_input, (size_t)le.L.in * 2, ys[j], (size_t)lj.L.out * 2)) ||
+              (lj.sel_input && overlap(ys[end], (size_t)le.L.out * 2, lj.sel_input, (size_t)lj.L.in * 2)) ||
               overlap(ys[end], (size_t)le.L.out * 2, xs[j], (size_t)lj.L.in * 2) ||
               overlap(ys[end], (size_t)le.L.out * 2, ys[j], (size_t)lj.L.out * 2);
       }
@@ -289,7 +292,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     for (int j = id; j < end; ++j) {
       const Linear& lin = m->linears[j];
       const Selector& s = lin.sel[lin.active];
-      SelJob sj = make_sel_job(lin, s, xs[j], e_dev + j, k_dev + j);
+      SelJob sj = make_sel_job(lin, s, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j);
       for (int part = 0; part < sj.nparts; ++part) sel_parts.push_back(SelPart{j - id, part});
       ws_offset.push_back(ws_slots);
       ws_slots += (size_t)sj.nparts;
@@ -509,6 +512,16 @@ int dpllm_set_active_pair(dpllm_model* m, int id, int l, int h) {
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
   lin->active = slot;
+  m->version++;
+  return DPLLM_OK;
+}
+
+int dpllm_set_selector_input(dpllm_model* m, int id, const void* xsel_dev) {
+  int rc = DPLLM_OK;
+  Linear* lin = get_linear(m, id, &rc);
+  if (!lin) return rc;
+  if ((uintptr_t)xsel_dev % 16) return fail(m, DPLLM_EINVAL, "selector input not 16-byte aligned");
+  lin->sel_input = xsel_dev;
   m->version++;
   return DPLLM_OK;
 }

@@ -253,6 +253,46 @@ def test_decode_step_matches_oracle(dp, mode):
 
 
 
+def test_decode_step_with_selector_inputs(dp):
+    """Asynchronous estimation (Sec. 5.2): some selectors read another vector (the previous residual); the
+    decisions follow that vector, the GEMVs still read the immediate inputs."""
+    shapes = [(128, 256), (64, 256), (320, 256), (256, 320)]
+    n_steps = 6
+    model, refs, xs_by_in = _step_model(dp, shapes, 5, 3, 4, 64, n_steps, seed=6100, mode="mixed")
+    n = len(shapes)
+    k_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(n, dtype=torch.float32, device="cuda")
+    prev = {in_: torch.zeros(in_, dtype=torch.float16, device="cuda") for in_ in xs_by_in}
+    for i in (0, 2):
+        model.dpllm_set_selector_input(i, prev[shapes[i][1]])
+    flips = 0
+    for t in range(1, n_steps):
+        for in_ in prev:
+            prev[in_].copy_(xs_by_in[in_][t - 1])
+        xs = [xs_by_in[in_][t].cuda() for _, in_ in shapes]
+        ys = [torch.empty(out, dtype=torch.float16, device="cuda") for out, _ in shapes]
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+        torch.cuda.synchronize()
+        x_np = [synth.lut_np(xs_by_in[in_][t]) for _, in_ in shapes]
+        xsel_np = [synth.lut_np(xs_by_in[in_][t - 1]) if i in (0, 2) else None for i, (_, in_) in enumerate(shapes)]
+        ry, rk, re = oracle.decode_step(refs, x_np, xsel_np)
+        _, rk_now, _ = oracle.decode_step(refs, x_np)
+        flips += int((rk != rk_now).sum())
+        assert k_dev.cpu().numpy().tolist() == rk.tolist()
+        assert np.allclose(e_dev.cpu().numpy(), re, rtol=3e-7)
+        for y, r in zip(ys, ry):
+            assert rel_l2(y.float().cpu().numpy(), r) <= REL_L2
+    assert flips > 0      # the two inputs really lead to different decisions somewhere
+    model.dpllm_set_selector_input(0, None)
+    model.dpllm_set_selector_input(2, None)
+    xs = [xs_by_in[in_][0].cuda() for _, in_ in shapes]
+    ys = [torch.empty(out, dtype=torch.float16, device="cuda") for out, _ in shapes]
+    model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+    _, rk, _ = oracle.decode_step(refs, [synth.lut_np(xs_by_in[in_][0]) for _, in_ in shapes])
+    assert k_dev.cpu().numpy().tolist() == rk.tolist()
+    model.close()
+
+
 def test_decode_step_chained_buffers_run_in_order(dp):
     """Linears that read what earlier ones write (o <- v, gate/up <- o, down <- gate) are ordered by the
     library: the result equals running them one after the other.  Bitwidths are pinned (alternating +/-inf) so

@@ -397,6 +397,22 @@ def test_decode_step_degenerate_and_mixed():
     assert math.isclose(oracle.effective_bits(ks, sizes), (3 * 512 + 4 * 768 + 3 * 768) / 2048.0)
 
 
+def test_decode_step_selector_input_moves_the_decision_not_the_product():
+    """Sec. 5.2: with a selector input the estimate is ||G x_sel|| (numpy matvec), the output is still W_k x."""
+    lins, xs = _tiny_model(lambda i, e: e)          # T = the estimate on the immediate input: selects l (not >)
+    assert oracle.decode_step(lins, xs)[1].tolist() == [3, 3, 3]
+    x_big = [(np.asarray(x).view(np.float16).astype(np.float32) * 2).astype(np.float16).view(np.uint16) for x in xs]
+    xs_sel = [None, x_big[1], None]
+    ys, ks, es = oracle.decode_step(lins, xs, xs_sel)
+    assert ks.tolist() == [3, 4, 3]                 # doubling the selector input doubles the estimate
+    G = lins[1]["selector"]["G"].view(np.float16).astype(np.float64)
+    want = np.linalg.norm(G @ x_big[1].view(np.float16).astype(np.float64))
+    assert math.isclose(es[1], want, rel_tol=1e-12)
+    assert (ys[1] == oracle.gemv(lins[1]["planes"], 4, lins[1]["luts"][4], xs[1])).all()
+    same = oracle.decode_step(lins, xs, [None, None, None])
+    assert same[1].tolist() == [3, 3, 3]
+
+
 # ----------------------------------------------------------------------------- P9 quantile calibration
 def test_quantile_threshold_realises_target_bits():
     lin = synth.make_linear(64, 128, 5, 3, seed=101)
