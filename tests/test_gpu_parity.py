@@ -421,3 +421,45 @@ def test_abi_error_paths(dp):
     assert dp.lib.dpllm_linear_device_bytes(8, 48, 4, 3, C.byref(n)) == dp.DPLLM_ESHAPE
     model.close()
     empty.close()
+
+
+# ----------------------------------------------------------------------------- T8 random shapes, long runs
+@pytest.mark.parametrize("seed", range(6))
+def test_gemv_random_shapes(dp, seed):
+    """Random odd shapes, every bitwidth the linear serves, random batch: ragged rows, ragged strips, short
+    and empty tails."""
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(4):
+        out = int(rng.integers(1, 600))
+        in_ = 32 * int(rng.integers(1, 300))
+        p = int(rng.integers(3, 9))
+        B = int(rng.integers(1, 6))
+        lin = synth.make_linear(out, in_, p, 3, seed=int(rng.integers(1 << 30)))
+        model = load(dp, [lin])
+        X = synth.make_x(in_, B, seed=int(rng.integers(1 << 30)))
+        planes = synth.planes_np(lin["planes"])
+        for k in range(3, p + 1):
+            ref = oracle.gemv(planes, k, synth.lut_np(lin["luts"][k]), synth.lut_np(X))
+            got = model.dpllm_gemv(0, k, (X if B > 1 else X[0]).cuda()).float().cpu().numpy().reshape(B, out)
+            for b in range(B):
+                assert rel_l2(got[b], ref[b]) <= REL_L2, (out, in_, p, k, B, b)
+        model.close()
+
+
+@pytest.mark.parametrize("out,in_", [(65600, 160), (65604, 4096)])
+def test_gemv_many_rows_several_row_quads_per_wavefront(dp, out, in_):
+    """More than 16384 row quads in one launch: every wavefront streams two or more row quads (table hand-over,
+    resident activations, ring across row-quad boundaries), batch 1 and 2."""
+    lin = synth.make_linear(out, in_, 5, 3, seed=out + in_, device="cuda", keep_codes=False)
+    model = dp.Model(1)
+    model.dpllm_load_linear(0, lin["planes"], lin["luts"], 3)
+    X = synth.make_x(in_, 2, seed=77)
+    planes = synth.planes_np(lin["planes"])
+    for k in (3, 4, 5):
+        lut = synth.lut_np(lin["luts"][k])
+        ref = oracle.gemv(planes, k, lut, synth.lut_np(X))
+        got1 = model.dpllm_gemv(0, k, X[0].cuda()).float().cpu().numpy()
+        got2 = model.dpllm_gemv(0, k, X.cuda()).float().cpu().numpy()
+        assert rel_l2(got1, ref[0]) <= REL_L2, k
+        assert rel_l2(got2[0], ref[0]) <= REL_L2 and rel_l2(got2[1], ref[1]) <= REL_L2, k
+    model.close()
