@@ -83,6 +83,7 @@ def main():
     ap.add_argument("--blocks", type=int, default=32, help="Transformer blocks (32 = the 7B shape)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-k sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches only (no HIP graph replay)")
     ap.add_argument("--copy-yardstick", action="store_true",
                     help="also run a plain 1 GiB copy kernel (for scaling hardware byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -111,7 +112,16 @@ def main():
     model, meta = build_model(dp, synth, torch, shapes, args.blocks, p, l, h, n_x, log=log)
     n = len(meta["shapes"])
     ins = sorted(meta["xs_by_in"])
-    xbuf = {in_: torch.empty(in_, dtype=torch.float16, device="cuda") for in_ in ins}
+    # the activation vectors of a step sit in one buffer (one copy per step); 128-byte aligned slices
+    offs, tot = {}, 0
+    for in_ in ins:
+        offs[in_] = tot
+        tot += (in_ + 63) // 64 * 64
+    xall = torch.zeros(tot, dtype=torch.float16, device="cuda")
+    xbuf = {in_: xall[offs[in_]:offs[in_] + in_] for in_ in ins}
+    xsteps = torch.zeros((n_x, tot), dtype=torch.float16, device="cuda")
+    for in_ in ins:
+        xsteps[:, offs[in_]:offs[in_] + in_] = meta["xs_by_in"][in_][:n_x]
     xs = [xbuf[in_] for _, in_ in meta["shapes"]]
     ys = [torch.empty(out, dtype=torch.float16, device="cuda") for out, _ in meta["shapes"]]
     x_tensors, y_tensors = xs, ys                     # keep the tensors alive; the calls take pointer arrays
@@ -120,8 +130,7 @@ def main():
     e_dev = torch.zeros(n, dtype=torch.float32, device="cuda")
 
     def set_inputs(t):
-        for in_ in ins:
-            xbuf[in_].copy_(meta["xs_by_in"][in_][t % n_x])
+        xall.copy_(xsteps[t % n_x])
 
     def timed(fn, steps, warmup):
         for t in range(warmup):
@@ -142,7 +151,30 @@ def main():
         set_inputs(t)
         model.dpllm_decode_step(xs, ys, k_dev, e_dev)
 
-    ms_step = timed(full_step, args.steps, args.warmup)
+    ms_step_eager = timed(full_step, args.steps, args.warmup)
+    ms_step, launch_mode = ms_step_eager, "eager launches"
+    if not args.no_graph:
+        # the same K steps recorded once in a HIP graph (per step: one input copy + three kernels) and replayed:
+        # what a serving loop does to shed launch gaps.  The replay's final state is checked against eager.
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for t in range(args.steps):
+                full_step(args.warmup + t)
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_graph = e0.elapsed_time(e1) / args.steps
+        k_graph, y_graph = k_dev.clone(), y_tensors[-1].clone()
+        full_step(args.warmup + args.steps - 1)
+        torch.cuda.synchronize()
+        if torch.equal(k_graph, k_dev) and torch.equal(y_graph, y_tensors[-1]):
+            ms_step, launch_mode = ms_graph, "one HIP graph of the K steps"
+        else:
+            log("graph replay differs from eager: reporting the eager time")
     # realised bitwidths over the activation set (untimed pass)
     params = np.array([o * i for o, i in meta["shapes"]], dtype=np.float64)
     step_bytes = []
@@ -232,6 +264,8 @@ def main():
                                "256 outlier-fp16 activation vectors, batch 1" % args.blocks,
                    "linears": n, "frac_of_hbm_peak": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "us_per_decode_step": round(ms_step * 1e3, 1),
+        "us_per_decode_step_eager": round(ms_step_eager * 1e3, 1),
+        "launch": launch_mode,
         "effective_bits": round(eff_bits, 4),
         "bytes_per_step": int(bytes_step),
         "selector": {"us_per_step": round(ms_sel * 1e3, 1), "GBps": round(sel_bytes / (ms_sel * 1e-3) / 1e9, 1),
