@@ -69,7 +69,18 @@ void dpllm_model_destroy(dpllm_model* m);
 /* Text of the last error on m (owned by m, valid until the next failing call). */
 const char* dpllm_last_error(const dpllm_model* m);
 
-/* Bytes of device arena one linear needs (planes + tables, 256-byte aligned parts).
+/* Private arrangement of the planes given to linears loaded after the call (both serve every entry point
+ * with identical results up to summation order):
+ *   DPLLM_LAYOUT_ROWQUAD (default): a lane owns 4 rows x 32 columns; a launch is cut into many small work
+ *     items, which suits single-linear launches;
+ *   DPLLM_LAYOUT_ROWLANE: a lane owns one row; table lookups are free of LDS bank conflicts (faster at 3 and
+ *     4 bits), work items are blocks of 64 rows, which suits launches of many linears (dpllm_decode_step).
+ * Errors: EINVAL. */
+#define DPLLM_LAYOUT_ROWQUAD 0
+#define DPLLM_LAYOUT_ROWLANE 1
+int dpllm_model_set_layout(dpllm_model* m, int layout);
+
+/* Bytes of device arena one linear needs (planes + tables, 256-byte aligned parts; enough for either layout).
  * Errors: EINVAL (bytes NULL), ESHAPE, ERANGE. */
 int dpllm_linear_device_bytes(int out, int in, int p, int kmin, size_t* bytes);
 

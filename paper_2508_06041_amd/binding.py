@@ -15,9 +15,10 @@ DPLLM_OK, DPLLM_EINVAL, DPLLM_ESHAPE, DPLLM_ERANGE, DPLLM_ESTATE, DPLLM_EHIP = 0
 DPLLM_SEL_NONE, DPLLM_SEL_PROJ, DPLLM_SEL_LINREG = 0, 1, 2
 DPLLM_MAX_BATCH = 8
 DPLLM_STEP_SELECT, DPLLM_STEP_GEMV = 1, 2
+DPLLM_LAYOUT_ROWQUAD, DPLLM_LAYOUT_ROWLANE = 0, 1
 
 SYMBOLS = ["dpllm_model_create", "dpllm_model_destroy", "dpllm_last_error", "dpllm_linear_device_bytes",
-           "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair", "dpllm_set_selector_input",
+           "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair", "dpllm_set_selector_input", "dpllm_model_set_layout",
            "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_copy", "dpllm_debug_read"]
 
 
@@ -44,6 +45,7 @@ def _load():
     L.dpllm_set_threshold.argtypes = [vp, i32, i32, i32, f32]
     L.dpllm_set_active_pair.argtypes = [vp, i32, i32, i32]
     L.dpllm_set_selector_input.argtypes = [vp, i32, vp]
+    L.dpllm_model_set_layout.argtypes = [vp, i32]
     L.dpllm_estimate.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
     L.dpllm_gemv.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp]
     L.dpllm_decode_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
@@ -98,12 +100,16 @@ def dpllm_debug_read(src, sink):
 class Model:
     """Owns the C handle and the torch tensors used as device arenas."""
 
-    def __init__(self, n_linears):
+    def __init__(self, n_linears, layout=None):
         h = C.c_void_p()
         rc = lib.dpllm_model_create(C.byref(h), n_linears)
         if rc != 0:
             raise DpllmError(rc, "dpllm_model_create")
         self.h = h
+        if layout is None and os.environ.get("DPLLM_LAYOUT"):
+            layout = {"rowquad": 0, "rowlane": 1}[os.environ["DPLLM_LAYOUT"]]
+        if layout is not None:
+            _check(self.h, lib.dpllm_model_set_layout(self.h, layout))
         self.n = n_linears
         self.arenas = {}
         self.keep = {}

@@ -11,21 +11,32 @@ namespace dpllm {
 
 __device__ __forceinline__ uint32_t rotr32(uint32_t v, int s) { return __builtin_rotateright32(v, s); }
 
-// canonical planes [p][out][ncw] -> device planes; one thread per (plane, row quad, column word)
+// canonical planes [p][out][ncw] -> device planes; one thread per (plane, row group, column word / tile):
+// it writes one 128-bit value (row quad: 4 rows x 1 word; row per lane: 1 row x 4 words)
 __global__ void retile_planes_kernel(const uint32_t* __restrict__ canon, uint4* __restrict__ dev,
-                                     int p, int out, int ncw, int nrq, size_t plane_stride_u4) {
-  size_t per_plane = (size_t)nrq * ncw;
+                                     int p, int out, int ncw, int ncc, int nrq, int row_lane, size_t plane_stride_u4) {
+  const size_t per_plane = row_lane ? (size_t)nrq * ncc * 64 : (size_t)nrq * ncw;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= per_plane * p) return;
   int b = (int)(i / per_plane);
   size_t e = i % per_plane;
-  int rq = (int)(e / ncw), cw = (int)(e % ncw);
   uint32_t w[4];
+  if (row_lane) {
+    const int o = (int)(e / ((size_t)ncc * 64)) * 64 + (int)(e % 64), cc = (int)(e / 64 % ncc);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    int o = rq * 4 + r;
-    uint32_t v = (o < out) ? canon[((size_t)b * out + o) * ncw + cw] : 0u;
-    w[r] = rotr32(permute_word(v), b);
+    for (int j = 0; j < 4; ++j) {
+      const int cw = cc * 4 + j;
+      uint32_t v = (o < out && cw < ncw) ? canon[((size_t)b * out + o) * ncw + cw] : 0u;
+      w[j] = rotr32(permute_word(v), b);
+    }
+  } else {
+    int rq = (int)(e / ncw), cw = (int)(e % ncw);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int o = rq * 4 + r;
+      uint32_t v = (o < out) ? canon[((size_t)b * out + o) * ncw + cw] : 0u;
+      w[r] = rotr32(permute_word(v), b);
+    }
   }
   dev[(size_t)b * plane_stride_u4 + e] = make_uint4(w[0], w[1], w[2], w[3]);
 }
@@ -41,16 +52,14 @@ __global__ void copy_lut_kernel(const uint16_t* __restrict__ src, uint16_t* __re
 }
 
 // device planes -> canonical k-bit codes uint8 [out][in]; one thread per (row, column word)
-__global__ void debug_unpack_kernel(const uint4* __restrict__ dev, size_t plane_stride_u4, int p, int k,
-                                    int out, int ncw, uint8_t* __restrict__ idx) {
+__global__ void debug_unpack_kernel(const uint32_t* __restrict__ dev, size_t plane_stride_u32, int p, int k,
+                                    int out, int ncw, int ncc, int row_lane, uint8_t* __restrict__ idx) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)out * ncw) return;
   int o = (int)(i / ncw), cw = (int)(i % ncw);
-  int rq = o / 4, r = o % 4;
   uint32_t w[8];
   for (int b = 0; b < p; ++b) {
-    uint4 v = dev[(size_t)b * plane_stride_u4 + (size_t)rq * ncw + cw];
-    uint32_t s = r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w;
+    uint32_t s = dev[(size_t)b * plane_stride_u32 + plane_word_index(row_lane, o, cw, ncw, ncc)];
     w[b] = unpermute_word((s << b) | (b ? (s >> (32 - b)) : 0u));  // undo rotation and permutation
   }
   for (int c = 0; c < 32; ++c) {

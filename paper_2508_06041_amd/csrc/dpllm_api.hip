@@ -15,6 +15,7 @@
 #include "aux_kernels.hpp"
 #include "gemv_fast.hpp"
 #include "gemv_kernels.hpp"
+#include "gemv_lane.hpp"
 #include "layout.hpp"
 #include "selector_kernels.hpp"
 
@@ -51,6 +52,7 @@ struct Linear {
 // running the linears strictly in order.
 struct GemvLaunch {
   int ka, kb;          // kernel instance; ka == kb == 0: the plain kernel, one launch per job
+  int mode;            // arrangement of the planes of the linears in this launch
   int first, count;    // slice of the device job table
   int blocks;
 };
@@ -77,6 +79,7 @@ struct dpllm_model {
   std::vector<Linear> linears;
   std::string err;
   uint64_t version = 1;            // bumped by every call that changes what a plan depends on
+  int layout = kLayoutRowQuad;     // arrangement given to linears loaded from now on
   // decode-step plan and its device tables
   StepPlan plan;
   SelJob* d_sel_jobs = nullptr;
@@ -166,8 +169,19 @@ void launch_fast_t(const GemvJob* d_jobs, int njobs, const GemvJob& one, int blo
   }
 }
 
-void launch_fast(int ka, int kb, const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
-#define DPLLM_CASE(A, B) case (A) * 16 + (B): launch_fast_t<A, B>(d_jobs, njobs, one, blocks, st); break;
+// row-per-lane arrangement: a batch runs one sample after the other inside the launch
+template <int KA, int KB>
+void launch_lane_t(const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
+  const int grid = d_jobs == nullptr ? one.nblocks * njobs : blocks;
+  hipLaunchKernelGGL((gemv_lane_kernel<KA, KB>), dim3(grid), dim3(kLaneThreads), 0, st, d_jobs, njobs, one);
+}
+
+void launch_fast(int mode, int ka, int kb, const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
+#define DPLLM_CASE(A, B)                                                            \
+  case (A) * 16 + (B):                                                              \
+    if (mode == kLayoutRowLane) launch_lane_t<A, B>(d_jobs, njobs, one, blocks, st); \
+    else launch_fast_t<A, B>(d_jobs, njobs, one, blocks, st);                       \
+    break;
   switch (ka * 16 + kb) {
     DPLLM_CASE(3, 3) DPLLM_CASE(4, 4) DPLLM_CASE(5, 5) DPLLM_CASE(6, 6) DPLLM_CASE(7, 7) DPLLM_CASE(8, 8)
     DPLLM_CASE(3, 4) DPLLM_CASE(4, 5) DPLLM_CASE(5, 6) DPLLM_CASE(6, 7) DPLLM_CASE(7, 8)
@@ -186,7 +200,7 @@ GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, c
   j.lut_off_a = (uint32_t)lin.L.lut_offset[ka];
   j.lut_off_b = (uint32_t)lin.L.lut_offset[kb];
   j.ka = ka; j.kb = kb;
-  j.out = lin.L.out; j.ncw = lin.L.ncw; j.nrq = lin.L.nrq;
+  j.out = lin.L.out; j.ncw = lin.L.ncw; j.nrq = lin.L.nrq; j.ncc = lin.L.ncc;
   j.nblocks = lin.L.nrq;
   j.block_start = 0;
   j.nsamples = 1;
@@ -195,8 +209,9 @@ GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, c
 
 // row quads one wavefront streams (workgroup b of a job takes row quads b, b + nblocks, ...): enough
 // wavefronts to fill the chip several times over, long enough runs to amortise the pipeline fill
-int pick_rq_per_block(long total_rq) {
-  long r = total_rq / 8192;
+int pick_rq_per_block(int mode, long total_rq) {
+  // row-per-lane: the unit is a block of 64 rows and a workgroup of eight wavefronts streams it
+  long r = total_rq / (mode == kLayoutRowLane ? 2048 : 8192);
   return (int)std::min<long>(8, std::max<long>(1, r));
 }
 
@@ -208,15 +223,16 @@ void launch_plain_t(const GemvArgs& a, hipStream_t st) {
 int launch_plain(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y,
                  int B, hipStream_t st) {
   GemvArgs a;
-  a.planes = lin.planes();
-  a.plane_stride_u4 = lin.L.plane_bytes / 16;
+  a.planes = (const uint32_t*)lin.arena;
+  a.plane_stride_u32 = lin.L.plane_bytes / 4;
   a.ka = ka; a.kb = kb;
   a.lut_a = lin.lut(ka);
   a.lut_b = k_dev ? lin.lut(kb) : nullptr;
   a.k_dev = k_dev;
   a.x = (const uint16_t*)x;
   a.y = (uint16_t*)y;
-  a.out = lin.L.out; a.in = lin.L.in; a.ncw = lin.L.ncw; a.nrq = lin.L.nrq;
+  a.out = lin.L.out; a.in = lin.L.in; a.ncw = lin.L.ncw; a.nrq = (lin.L.out + 3) / 4;
+  a.ncc = lin.L.ncc; a.row_lane = lin.L.mode == kLayoutRowLane;
   switch (B) {
     case 1: launch_plain_t<1>(a, st); break;
     case 2: launch_plain_t<2>(a, st); break;
@@ -236,9 +252,9 @@ int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t
                 int B, hipStream_t st) {
   if (!has_fast_kernel(ka, kb)) return launch_plain(m, lin, ka, kb, k_dev, x, y, B, st);
   GemvJob j = make_gemv_job(lin, ka, kb, k_dev, x, y);
-  const int rpb = pick_rq_per_block(lin.L.nrq);
+  const int rpb = pick_rq_per_block(lin.L.mode, lin.L.nrq);
   j.nblocks = (lin.L.nrq + rpb - 1) / rpb;
-  launch_fast(ka, kb, nullptr, B, j, j.nblocks * B, st);
+  launch_fast(lin.L.mode, ka, kb, nullptr, B, j, j.nblocks * B, st);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -299,30 +315,31 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       sel_jobs.push_back(sj);
     }
     ph.part_count = (int)sel_parts.size() - ph.part_first;
-    // GEMV jobs of the phase, grouped by kernel instance in order of first appearance
-    std::vector<std::pair<int, int>> classes;
+    // GEMV jobs of the phase, grouped by kernel instance (bitwidth pair, arrangement) in order of first appearance
+    struct Cls { int ka, kb, mode; bool operator==(const Cls& o) const { return ka == o.ka && kb == o.kb && mode == o.mode; } };
+    auto cls_of = [&](int j) {
+      const Linear& lj = m->linears[j];
+      const Selector& s = lj.sel[lj.active];
+      return has_fast_kernel(s.l, s.h) ? Cls{s.l, s.h, lj.L.mode} : Cls{0, 0, 0};
+    };
+    std::vector<Cls> classes;
     for (int j = id; j < end; ++j) {
-      const Selector& s = m->linears[j].sel[m->linears[j].active];
-      std::pair<int, int> c = has_fast_kernel(s.l, s.h) ? std::make_pair(s.l, s.h) : std::make_pair(0, 0);
+      Cls c = cls_of(j);
       if (std::find(classes.begin(), classes.end(), c) == classes.end()) classes.push_back(c);
     }
-    for (auto c : classes) {
+    for (const Cls& c : classes) {
       GemvLaunch gl;
-      gl.ka = c.first; gl.kb = c.second;
+      gl.ka = c.ka; gl.kb = c.kb; gl.mode = c.mode;
       gl.first = (int)P.gemv_jobs.size();
       long total_rq = 0;
-      for (int j = id; j < end; ++j) {
-        const Selector& s = m->linears[j].sel[m->linears[j].active];
-        bool fast = has_fast_kernel(s.l, s.h);
-        if ((fast && s.l == c.first && s.h == c.second) || (!fast && c.first == 0)) total_rq += m->linears[j].L.nrq;
-      }
-      const int rpb = pick_rq_per_block(total_rq);
+      for (int j = id; j < end; ++j)
+        if (cls_of(j) == c) total_rq += m->linears[j].L.nrq;
+      const int rpb = pick_rq_per_block(c.mode, total_rq);
       int blocks = 0;
       for (int j = id; j < end; ++j) {
+        if (!(cls_of(j) == c)) continue;
         const Linear& lin = m->linears[j];
         const Selector& s = lin.sel[lin.active];
-        bool fast = has_fast_kernel(s.l, s.h);
-        if (!((fast && s.l == c.first && s.h == c.second) || (!fast && c.first == 0))) continue;
         GemvJob gj = make_gemv_job(lin, s.l, s.h, s.l == s.h ? nullptr : k_dev + j, xs[j], ys[j]);
         gj.nblocks = (lin.L.nrq + rpb - 1) / rpb;
         gj.block_start = blocks;
@@ -398,7 +415,9 @@ int dpllm_linear_device_bytes(int out, int in, int p, int kmin, size_t* bytes) {
   if (!bytes) return DPLLM_EINVAL;
   int rc = check_shape(out, in, p, kmin);
   if (rc != DPLLM_OK) return rc;
-  *bytes = LinearLayout::make(out, in, p, kmin).total_bytes;
+  // enough for either arrangement of the planes
+  *bytes = std::max(LinearLayout::make(out, in, p, kmin, kLayoutRowQuad).total_bytes,
+                    LinearLayout::make(out, in, p, kmin, kLayoutRowLane).total_bytes);
   return DPLLM_OK;
 }
 
@@ -414,7 +433,7 @@ int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin, 
   for (int k = kmin; k <= p; ++k)
     if (!luts[k - kmin]) return fail(m, DPLLM_EINVAL, "null table for k=%d", k);
   if ((uintptr_t)dev_arena % kAlign) return fail(m, DPLLM_EINVAL, "arena not %zu-byte aligned", kAlign);
-  LinearLayout L = LinearLayout::make(out, in, p, kmin);
+  LinearLayout L = LinearLayout::make(out, in, p, kmin, m->layout);
   if (arena_bytes < L.total_bytes)
     return fail(m, DPLLM_ESTATE, "arena holds %zu bytes, %zu needed", arena_bytes, L.total_bytes);
   hipStream_t st = (hipStream_t)stream;
@@ -437,16 +456,17 @@ int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin, 
     d_planes = (const uint32_t*)staging;
   }
   {
-    size_t n = (size_t)L.nrq * L.ncw * p;
+    const int row_lane = L.mode == kLayoutRowLane;
+    size_t n = (row_lane ? (size_t)L.nrq * L.ncc * 64 : (size_t)L.nrq * L.ncw) * p;
     hipLaunchKernelGGL(retile_planes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_planes,
-                       (uint4*)dev_arena, p, out, L.ncw, L.nrq, L.plane_bytes / 16);
+                       (uint4*)dev_arena, p, out, L.ncw, L.ncc, L.nrq, row_lane, L.plane_bytes / 16);
   }
   const char* lsrc = staging ? (const char*)staging + plane_words * 4 : nullptr;
   for (int k = kmin; k <= p; ++k) {
     const uint16_t* src = staging ? (const uint16_t*)lsrc : luts[k - kmin];
-    size_t n = (size_t)L.nrq * 4 << k;
+    size_t n = (size_t)L.rows_padded << k;
     hipLaunchKernelGGL(copy_lut_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src,
-                       (uint16_t*)((char*)dev_arena + L.lut_offset[k]), out, L.nrq * 4, 1 << k);
+                       (uint16_t*)((char*)dev_arena + L.lut_offset[k]), out, L.rows_padded, 1 << k);
     if (staging) lsrc += ((size_t)out << k) * 2;
   }
   hipError_t e = hipGetLastError();
@@ -513,6 +533,13 @@ int dpllm_set_active_pair(dpllm_model* m, int id, int l, int h) {
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
   lin->active = slot;
   m->version++;
+  return DPLLM_OK;
+}
+
+int dpllm_model_set_layout(dpllm_model* m, int layout) {
+  if (!m) return DPLLM_EINVAL;
+  if (layout != DPLLM_LAYOUT_ROWQUAD && layout != DPLLM_LAYOUT_ROWLANE) return fail(m, DPLLM_EINVAL, "unknown layout %d", layout);
+  m->layout = layout == DPLLM_LAYOUT_ROWLANE ? kLayoutRowLane : kLayoutRowQuad;
   return DPLLM_OK;
 }
 
@@ -600,7 +627,7 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
     if (!(parts & DPLLM_STEP_GEMV)) continue;
     for (const GemvLaunch& gl : ph.gemv) {
       if (gl.ka != 0) {
-        launch_fast(gl.ka, gl.kb, m->d_gemv_jobs + gl.first, gl.count, gnone, gl.blocks, st);
+        launch_fast(gl.mode, gl.ka, gl.kb, m->d_gemv_jobs + gl.first, gl.count, gnone, gl.blocks, st);
       } else {
         for (int i = gl.first; i < gl.first + gl.count; ++i) {
           const GemvJob& j = P.gemv_jobs[i];
@@ -627,7 +654,8 @@ int dpllm_debug_unpack(dpllm_model* m, int id, int k, uint8_t* idx_dev, void* st
   if (k < 1 || k > lin->L.p) return fail(m, DPLLM_ERANGE, "k=%d outside [1,%d]", k, lin->L.p);
   size_t n = (size_t)lin->L.out * lin->L.ncw;
   hipLaunchKernelGGL(debug_unpack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                     lin->planes(), lin->L.plane_bytes / 16, lin->L.p, k, lin->L.out, lin->L.ncw, idx_dev);
+                     (const uint32_t*)lin->arena, lin->L.plane_bytes / 4, lin->L.p, k, lin->L.out, lin->L.ncw, lin->L.ncc,
+                     (int)(lin->L.mode == kLayoutRowLane), idx_dev);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }

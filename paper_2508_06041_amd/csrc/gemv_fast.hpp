@@ -46,6 +46,7 @@ struct GemvJob {
   int32_t nblocks;            // workgroups of this job; workgroup b streams row quads b, b + nblocks, ...
   int32_t block_start;        // index of this job's first workgroup inside a multi-job grid
   int32_t nsamples;           // right-hand sides served together (1..NB): sample s reads x + s * in, writes y + s * out
+  int32_t ncc;                // row-per-lane layout: 128-column tiles per row (there nrq counts blocks of 64 rows)
 };
 
 __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
@@ -106,9 +107,9 @@ struct Decode {
 };
 
 // planes of one row -> eight words, each four byte-aligned fields [code << shift]
-template <int K>
+template <int K, int D = Decode<K>::d>
 __device__ __forceinline__ void merge_byte_fields(const uint32_t (&w)[K], uint32_t (&R)[8]) {
-  constexpr int d = Decode<K>::d;
+  constexpr int d = D;
   uint32_t v[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) v[s] = (s >= d && s < d + K) ? w[(s >= d && s < d + K) ? s - d : 0] : 0u;

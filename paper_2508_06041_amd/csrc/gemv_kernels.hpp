@@ -12,15 +12,16 @@
 namespace dpllm {
 
 struct GemvArgs {
-  const uint4* planes;       // device planes, plane b at planes + b * plane_stride_u4
-  size_t plane_stride_u4;
+  const uint32_t* planes;    // device planes, plane b at planes + b * plane_stride_u32
+  size_t plane_stride_u32;
   const uint16_t* lut_a;     // table of bitwidth ka, [nrq*4][2^ka]
   const uint16_t* lut_b;     // table of bitwidth kb (dynamic selection) or nullptr
   int ka, kb;
   const int32_t* k_dev;      // nullptr: use ka; else *k_dev in {ka, kb}
   const uint16_t* x;         // fp16 [B][in]
   uint16_t* y;               // fp16 [B][out]
-  int out, in, ncw, nrq;
+  int out, in, ncw, nrq;     // nrq: row quads (ceil(out / 4)) whatever the arrangement
+  int ncc, row_lane;         // arrangement of the words inside a plane (see layout_device.hpp)
 };
 
 // Plain kernel: one wave per row quad, one code bit at a time.  Serves every (k, B).
@@ -42,7 +43,13 @@ __global__ void __launch_bounds__(256) gemv_plain_kernel(GemvArgs a) {
     for (int b = 0; b < B; ++b) acc[r][b] = 0.f;
   for (int cw = lane; cw < a.ncw; cw += 64) {
     uint4 w[8];
-    for (int b = 0; b < k; ++b) w[b] = a.planes[(size_t)b * a.plane_stride_u4 + (size_t)rq * a.ncw + cw];
+    for (int b = 0; b < k; ++b) {
+      const uint32_t* pl = a.planes + (size_t)b * a.plane_stride_u32;
+      w[b].x = pl[plane_word_index(a.row_lane, rq * 4 + 0, cw, a.ncw, a.ncc)];
+      w[b].y = pl[plane_word_index(a.row_lane, rq * 4 + 1, cw, a.ncw, a.ncc)];
+      w[b].z = pl[plane_word_index(a.row_lane, rq * 4 + 2, cw, a.ncw, a.ncc)];
+      w[b].w = pl[plane_word_index(a.row_lane, rq * 4 + 3, cw, a.ncw, a.ncc)];
+    }
     for (int q = 0; q < 32; ++q) {
       uint32_t code[4] = {0, 0, 0, 0};
       for (int b = 0; b < k; ++b) {

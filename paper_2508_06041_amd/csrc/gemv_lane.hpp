@@ -1,0 +1,425 @@
+// Any-precision GEMV for gfx950, row-per-lane variant: y[o] = sum_c LUT_k[o][code_k(o,c)] * x[c]   (paper Sec. 3:
+// the linear operation of a decode step; Sec. 2.2: the k-bit model is the top k planes of the parent).
+//
+// Layout (kLayoutRowLane): a plane is cut into tiles of 64 rows x 128 columns; lane l of a wavefront owns row
+// 64 rb + l of the tile and reads its four 32-column words with one 128-bit load, so a wavefront load is 1 KiB
+// of contiguous memory per plane.  Words are permuted and rotated as in layout_device.hpp.
+//
+// Why rows on lanes: every lane looks its weights up in its own row's table.  The tables of the 64 rows are
+// interleaved in LDS (entry e of row l at byte e * 256 + l * 4), so lane l only ever touches bank l mod 32 and
+// lookups are free of bank conflicts whatever the table size; the two-weight tables of k = 3 and k = 4, which
+// cost 4 - 6 LDS cycles per lookup when a whole wavefront shares one row's table, cost 2.
+// The activations are the same for all lanes.  A lane loads 16 bytes of them per word (lane l takes the
+// pairs 4 (l mod 4) .. + 3), and the multiply-add reads the pair it needs from the right lane of its quad with
+// a DPP quad broadcast: 16 registers hold the 64 activation pairs of a tile.
+// Each lane accumulates its own row: no cross-lane reduction.  A workgroup is eight wavefronts that split the
+// columns of the same 64 rows and share the tables; their eight partial sums per row meet in LDS.
+//
+//   k = 3, 4 : two weights per lookup, tables of 64 / 256 fp16 pairs per row (16 / 64 KiB per workgroup)
+//   k >= 5   : one weight per lookup (table of 2^k entries per row, 8 .. 64 KiB), two results packed for one
+//              v_dot2_f32_f16
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "gemv_fast.hpp"
+#include "layout_device.hpp"
+
+namespace dpllm {
+
+constexpr int kLaneWaves = 8;            // wavefronts per workgroup
+constexpr int kLaneThreads = 64 * kLaneWaves;
+
+template <int K>
+struct LaneDecode {
+  static constexpr bool pair = K <= 4;                        // two weights per lookup
+  static constexpr int entries = pair ? (1 << (2 * K)) : (1 << K);
+  static constexpr int table_bytes = entries * 256;           // 64 rows interleaved, 4 bytes per row and entry
+  static constexpr int share = entries / kLaneWaves;          // entries a wavefront builds per row block
+  // single-weight schemes: the byte of column `col` is its code; which of the eight merged words, which byte
+  static constexpr int d = 8 - K;
+  __host__ __device__ static constexpr int top(int col) { return (col_to_pos(col) + d) & 31; }
+  __host__ __device__ static constexpr int word(int col) { return top(col) & 7; }
+  __host__ __device__ static constexpr int rot(int c) { return (c + 1) & 7; }
+  __host__ __device__ static constexpr int byte(int col) { return ((top(col) - rot(word(col))) & 31) >> 3; }
+};
+template <int KA, int KB>
+__host__ __device__ constexpr int lane_lds_bytes() {
+  constexpr int a = LaneDecode<KA>::table_bytes, b = LaneDecode<KB>::table_bytes;
+  return (a > b ? a : b) + kLaneWaves * 64 * 4;               // + the partial sums of the eight wavefronts
+}
+
+// x pair held by lane Q of the quad, times the looked-up pair, added to acc
+template <int Q>
+__device__ __forceinline__ void dot2_quad(float& acc, uint32_t xreg, uint32_t wpair) {
+  static_assert(Q >= 0 && Q < 4, "quad lane");
+  if constexpr (Q == 0) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+  if constexpr (Q == 1) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+  if constexpr (Q == 2) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+  if constexpr (Q == 3) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+}
+
+// LDS address of entry (byte N of t) in the lane's table column: byte 1 = the entry, byte 0 = lane * 4
+template <int N>
+__device__ __forceinline__ uint32_t lane_entry_addr(uint32_t t, uint32_t lanecol) {
+  constexpr uint32_t sel = 0x0c0c0000u | ((4u + N) << 8);   // {0, 0, t.byteN, lanecol.byte0}
+  return __builtin_amdgcn_perm(t, lanecol, sel);
+}
+
+__device__ __forceinline__ uint32_t lds_u32(const char* lds, uint32_t addr) { return *reinterpret_cast<const uint32_t*>(lds + addr); }
+
+// ---- a tile: the lane's row, 128 columns ------------------------------------------------------------------
+// x[j]: the lane's share of the activation pairs of word j.  k != 4: natural pairs (2i, 2i+1), lane q of a quad
+// holds i = 4 q .. 4 q + 3.  k = 4: the two 16-byte blocks the lane's four pairs (16 a + b: two columns 14 - 22
+// apart) are cut from, re-paired by lane_pair_x4 before use.
+template <int K>
+struct LaneTile {
+  u32x4 w[K];
+  u32x4 x[K == 4 ? 8 : 4];
+};
+
+struct LaneCtx {
+  uint32_t lanecol;     // lane * 4: the lane's column of the interleaved tables
+  int xa, xb;           // k = 4: 16-byte block numbers (inside a word's 64 bytes) of the lane's two activation blocks
+  uint32_t xsel;        // k = 4: byte selector that packs the wanted halves
+  bool xodd;            // k = 4: odd quad lanes take the second block rotated by one pair
+};
+
+__device__ __forceinline__ LaneCtx lane_ctx(int lane) {
+  LaneCtx c;
+  c.lanecol = (uint32_t)lane * 4;
+  const int q = lane & 3;
+  // quad lane q serves the pairs of merged word q (see nibble_pair_col_hi / _lo): upper-nibble columns come
+  // from natural pairs {8.., 4.., 12.., 0..}[q], lower-nibble columns from {0.., 12.., 4.., 8..}[q]
+  c.xa = q == 0 ? 2 : q == 1 ? 1 : q == 2 ? 3 : 0;
+  c.xb = q == 0 ? 0 : q == 1 ? 3 : q == 2 ? 1 : 2;
+  c.xodd = (q & 1) != 0;
+  c.xsel = c.xodd ? 0x05040100u : 0x07060302u;   // odd: the even columns (low halves); even: the odd columns
+  return c;
+}
+
+template <int K>
+__device__ __forceinline__ void lane_load_tile(LaneTile<K>& t, const GemvJob& job, const LaneCtx& ctx, int rb, int cc, int lane) {
+  const DPLLM_GLOBAL u32x4* p = as_global(reinterpret_cast<const u32x4*>(job.arena)) + ((size_t)rb * job.ncc + cc) * 64 + lane;
+#pragma unroll
+  for (int b = 0; b < K; ++b) t.w[b] = load_stream(p + (size_t)b * job.plane_stride_u4);
+  const DPLLM_GLOBAL u32x4* xp = as_global(reinterpret_cast<const u32x4*>(job.x));
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int cw = min(cc * 4 + j, job.ncw - 1);   // words past the end of the row: clamped here, zeroed before use
+    if constexpr (K == 4) {
+      t.x[2 * j] = xp[(size_t)cw * 4 + ctx.xa];
+      t.x[2 * j + 1] = xp[(size_t)cw * 4 + ctx.xb];
+    } else {
+      t.x[j] = xp[(size_t)cw * 4 + (lane & 3)];
+    }
+  }
+}
+
+// words past the end of a ragged row hold zero codes, whose centroid is not zero: their activations are zeroed
+template <int K>
+__device__ __forceinline__ void lane_zero_tail(LaneTile<K>& t, int cc, int ncw) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (cc * 4 + j >= ncw) {
+      if constexpr (K == 4) { t.x[2 * j] = u32x4{0u, 0u, 0u, 0u}; t.x[2 * j + 1] = u32x4{0u, 0u, 0u, 0u}; }
+      else t.x[j] = u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+// k = 4: pairs (x[col_hi], x[col_lo]) of merged word q = quad lane, byte m = register m
+__device__ __forceinline__ u32x4 lane_pair_x4(const u32x4& a, const u32x4& b, const LaneCtx& ctx) {
+  const uint32_t b0 = ctx.xodd ? b.w : b.x, b1 = ctx.xodd ? b.x : b.y, b2 = ctx.xodd ? b.y : b.z, b3 = ctx.xodd ? b.z : b.w;
+  u32x4 r;
+  r.x = __builtin_amdgcn_perm(b0, a.x, ctx.xsel);
+  r.y = __builtin_amdgcn_perm(b1, a.y, ctx.xsel);
+  r.z = __builtin_amdgcn_perm(b2, a.z, ctx.xsel);
+  r.w = __builtin_amdgcn_perm(b3, a.w, ctx.xsel);
+  return r;
+}
+
+// ---- entry words of one 32-column word -----------------------------------------------------------------------
+// k = 3: four words of four bytes (8 a + b), the pairs (2i, 2i+1), i = 4 jj + n
+__device__ __forceinline__ void lane_entries3(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t (&T)[4]) {
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const uint32_t m0 = rotl_c(0x90909090u, 2 * jj), m1 = rotl_c(0x48484848u, 2 * jj), m2 = rotl_c(0x24242424u, 2 * jj);
+    T[jj] = __builtin_rotateright32(bfi_insn(m0, w0, bfi_insn(m1, w1, w2 & m2)), 2 * jj + 2);
+  }
+}
+
+// two-weight schemes: eight lookups from entry words JA, JA + 1
+template <int JA>
+__device__ __forceinline__ void lane_issue_pairs(const uint32_t (&T)[4], uint32_t lanecol, const char* lds, uint32_t (&v)[8]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t t = T[JA + h];
+    v[4 * h + 0] = lds_u32(lds, lane_entry_addr<0>(t, lanecol));
+    v[4 * h + 1] = lds_u32(lds, lane_entry_addr<1>(t, lanecol));
+    v[4 * h + 2] = lds_u32(lds, lane_entry_addr<2>(t, lanecol));
+    v[4 * h + 3] = lds_u32(lds, lane_entry_addr<3>(t, lanecol));
+  }
+}
+
+// last lookup first: LDS answers in issue order, so one counter wait covers the eight
+template <int JA>
+__device__ __forceinline__ void lane_consume_pairs(const uint32_t (&v)[8], const u32x4& x, float (&acc)[4]) {
+  dot2_quad<JA + 1>(acc[3], x.w, v[7]);
+  dot2_quad<JA + 1>(acc[2], x.z, v[6]);
+  dot2_quad<JA + 1>(acc[1], x.y, v[5]);
+  dot2_quad<JA + 1>(acc[0], x.x, v[4]);
+  dot2_quad<JA>(acc[3], x.w, v[3]);
+  dot2_quad<JA>(acc[2], x.z, v[2]);
+  dot2_quad<JA>(acc[1], x.y, v[1]);
+  dot2_quad<JA>(acc[0], x.x, v[0]);
+}
+
+// single-weight schemes: the eight lookups of columns 8 JJ .. 8 JJ + 7
+template <int K, int JJ>
+__device__ __forceinline__ void lane_issue_singles(const uint32_t (&R)[8], uint32_t lanecol, const char* lds, uint32_t (&v)[8]) {
+  using D = LaneDecode<K>;
+#define DPLLM_LANE_LOOKUP(N)                                                                        \
+  {                                                                                                 \
+    constexpr int ce = 8 * JJ + 2 * N, co = ce + 1;                                                 \
+    v[2 * N] = lds_u32(lds, lane_entry_addr<D::byte(ce)>(R[D::word(ce)], lanecol));                 \
+    v[2 * N + 1] = lds_u32(lds, lane_entry_addr<D::byte(co)>(R[D::word(co)], lanecol));             \
+  }
+  DPLLM_LANE_LOOKUP(0) DPLLM_LANE_LOOKUP(1) DPLLM_LANE_LOOKUP(2) DPLLM_LANE_LOOKUP(3)
+#undef DPLLM_LANE_LOOKUP
+}
+
+// a table entry is an fp16 in the low half of a dword: two of them pack into one fp16 pair
+template <int JJ>
+__device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], const u32x4& x, float (&acc)[4]) {
+  dot2_quad<JJ>(acc[3], x.w, v[6] | (v[7] << 16));
+  dot2_quad<JJ>(acc[2], x.z, v[4] | (v[5] << 16));
+  dot2_quad<JJ>(acc[1], x.y, v[2] | (v[3] << 16));
+  dot2_quad<JJ>(acc[0], x.x, v[0] | (v[1] << 16));
+}
+
+// ---- one tile -------------------------------------------------------------------------------------------------
+// Lookups run in chunks of eight; the next chunk's lookups are issued before the current chunk's multiply-adds.
+template <int K>
+__device__ __forceinline__ void lane_compute(const LaneTile<K>& t, const LaneCtx& ctx, const char* lds, float (&acc)[4]) {
+  const uint32_t lanecol = ctx.lanecol;
+  uint32_t va[8], vb[8];
+  if constexpr (LaneDecode<K>::pair) {
+    uint32_t T[4][4];
+    u32x4 xq[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if constexpr (K == 3) {
+        lane_entries3(t.w[0][j], t.w[1][j], t.w[2][j], T[j]);
+        xq[j] = t.x[j];
+      } else {
+        const uint32_t w[4] = {t.w[0][j], t.w[1][j], t.w[2][j], t.w[3][j]};
+        merge_nibble_pairs(w, T[j]);
+        xq[j] = lane_pair_x4(t.x[2 * j], t.x[2 * j + 1], ctx);
+      }
+    }
+    lane_issue_pairs<0>(T[0], lanecol, lds, va);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      lane_issue_pairs<2>(T[j], lanecol, lds, vb);
+      sched_fence();
+      lane_consume_pairs<0>(va, xq[j], acc);
+      sched_fence();
+      if (j + 1 < 4) lane_issue_pairs<0>(T[j + 1], lanecol, lds, va);
+      sched_fence();
+      lane_consume_pairs<2>(vb, xq[j], acc);
+      sched_fence();
+    }
+  } else {
+    uint32_t R[2][8];
+    {
+      uint32_t w[K];
+#pragma unroll
+      for (int b = 0; b < K; ++b) w[b] = t.w[b][0];
+      merge_byte_fields<K, LaneDecode<K>::d>(w, R[0]);
+    }
+    lane_issue_singles<K, 0>(R[0], lanecol, lds, va);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j + 1 < 4) {
+        uint32_t w[K];
+#pragma unroll
+        for (int b = 0; b < K; ++b) w[b] = t.w[b][(j + 1) & 3];
+        merge_byte_fields<K, LaneDecode<K>::d>(w, R[(j + 1) & 1]);
+      }
+      lane_issue_singles<K, 1>(R[j & 1], lanecol, lds, vb);
+      sched_fence();
+      lane_consume_singles<0>(va, t.x[j], acc);
+      sched_fence();
+      lane_issue_singles<K, 2>(R[j & 1], lanecol, lds, va);
+      sched_fence();
+      lane_consume_singles<1>(vb, t.x[j], acc);
+      sched_fence();
+      lane_issue_singles<K, 3>(R[j & 1], lanecol, lds, vb);
+      sched_fence();
+      lane_consume_singles<2>(va, t.x[j], acc);
+      sched_fence();
+      if (j + 1 < 4) lane_issue_singles<K, 0>(R[(j + 1) & 1], lanecol, lds, va);
+      sched_fence();
+      lane_consume_singles<3>(vb, t.x[j], acc);
+      sched_fence();
+    }
+  }
+}
+
+// ---- tables -------------------------------------------------------------------------------------------------
+// The lane's row of the k-bit table (the part this wavefront builds entries from), fetched one row block ahead.
+//   k = 3: the whole row (8 fp16); k = 4: the whole row (16 fp16); k >= 5: entries [share * wave, + share)
+template <int K>
+struct LaneLut {
+  static constexpr int kDwords = K == 3 ? 4 : K == 4 ? 8 : LaneDecode<K>::share / 2;
+  uint32_t v[kDwords];
+};
+
+template <int K>
+__device__ __forceinline__ void lane_fetch_lut(LaneLut<K>& L, const DPLLM_GLOBAL uint16_t* lut_base, int rb, int lane, int wave) {
+  const DPLLM_GLOBAL uint32_t* row = reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(lut_base + (((size_t)rb * 64 + lane) << K));
+  const DPLLM_GLOBAL uint32_t* src = K <= 4 ? row : row + wave * LaneLut<K>::kDwords;
+  if constexpr (LaneLut<K>::kDwords >= 4) {
+#pragma unroll
+    for (int i = 0; i < LaneLut<K>::kDwords / 4; ++i) {
+      const u32x4 q = reinterpret_cast<const DPLLM_GLOBAL u32x4*>(src)[i];
+      L.v[4 * i] = q.x; L.v[4 * i + 1] = q.y; L.v[4 * i + 2] = q.z; L.v[4 * i + 3] = q.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < LaneLut<K>::kDwords; ++i) L.v[i] = src[i];
+  }
+}
+
+// half h (0 = low) of dword d, for a wavefront-uniform h
+__device__ __forceinline__ uint32_t half_of(uint32_t d, int h) { return h ? d >> 16 : d & 0xffffu; }
+
+template <int K>
+__device__ __forceinline__ void lane_build_table(const LaneLut<K>& L, int wave, uint32_t lanecol, char* lds) {
+  if constexpr (K == 3) {
+    // wavefront w writes the entries (a = w, b = 0..7): (LUT[a], LUT[b])
+    const uint32_t lw = wave < 2 ? L.v[0] : wave < 4 ? L.v[1] : wave < 6 ? L.v[2] : L.v[3];
+    const uint32_t la = half_of(lw, wave & 1);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const uint32_t hb = (b & 1) ? (L.v[b >> 1] & 0xffff0000u) : (L.v[b >> 1] << 16);
+      *reinterpret_cast<uint32_t*>(lds + (uint32_t)(wave * 8 + b) * 256 + lanecol) = la | hb;
+    }
+  } else if constexpr (K == 4) {
+    // wavefront w writes the entries (a = 2 w + s, b = 0..15), s = 0, 1
+    uint32_t lw = L.v[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) lw = wave == i ? L.v[i] : lw;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const uint32_t la = s ? lw >> 16 : lw & 0xffffu;
+#pragma unroll
+      for (int b = 0; b < 16; ++b) {
+        const uint32_t hb = (b & 1) ? (L.v[b >> 1] & 0xffff0000u) : (L.v[b >> 1] << 16);
+        *reinterpret_cast<uint32_t*>(lds + (uint32_t)((wave * 2 + s) * 16 + b) * 256 + lanecol) = la | hb;
+      }
+    }
+  } else {
+    // wavefront w writes its share of the entries, an fp16 in the low half of a dword
+    constexpr int share = LaneDecode<K>::share;
+#pragma unroll
+    for (int e = 0; e < share; ++e) {
+      const uint32_t v = (e & 1) ? L.v[e >> 1] >> 16 : L.v[e >> 1] & 0xffffu;
+      *reinterpret_cast<uint32_t*>(lds + (uint32_t)(wave * share + e) * 256 + lanecol) = v;
+    }
+  }
+}
+
+__device__ __forceinline__ void lane_group_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// One workgroup: row blocks block, block + nblocks, ... of a job; wavefront w takes the column tiles
+// [w ncc / 8, (w + 1) ncc / 8) of every row block.  Tile loads run one tile ahead, also across row blocks.
+template <int K>
+__device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int tid, char* lds) {
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const LaneCtx ctx = lane_ctx(lane);
+  float* red = reinterpret_cast<float*>(lds + LaneDecode<K>::table_bytes);
+  const int c0 = wave * job.ncc / kLaneWaves, c1 = (wave + 1) * job.ncc / kLaneWaves;
+  const int nrb = job.nrq;                     // row blocks of the job
+  const DPLLM_GLOBAL uint16_t* lut_base = as_global(reinterpret_cast<const uint16_t*>(job.arena + lut_off));
+  const bool ragged = (job.ncw & 3) != 0;
+  LaneTile<K> ta, tb;
+  LaneLut<K> L;
+  lane_fetch_lut<K>(L, lut_base, block, lane, wave);
+  if (c0 < c1) lane_load_tile<K>(ta, job, ctx, block, c0, lane);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int rb = block; rb < nrb; rb += job.nblocks) {
+    lane_build_table<K>(L, wave, ctx.lanecol, lds);
+    const int rbn = rb + job.nblocks < nrb ? rb + job.nblocks : rb;
+    lane_fetch_lut<K>(L, lut_base, rbn, lane, wave);
+    lane_group_barrier();
+    for (int cc = c0; cc < c1; cc += 2) {
+      {  // tile in ta; the next one travels into tb
+        const bool more = cc + 1 < c1;
+        lane_load_tile<K>(tb, job, ctx, more ? rb : rbn, more ? cc + 1 : c0, lane);
+        if (ragged && cc == job.ncc - 1) lane_zero_tail<K>(ta, cc, job.ncw);
+        lane_compute<K>(ta, ctx, lds, acc);
+      }
+      if (cc + 1 < c1) {  // tile in tb; the next one travels into ta
+        const bool more = cc + 2 < c1;
+        lane_load_tile<K>(ta, job, ctx, more ? rb : rbn, more ? cc + 2 : c0, lane);
+        if (ragged && cc + 1 == job.ncc - 1) lane_zero_tail<K>(tb, cc + 1, job.ncw);
+        lane_compute<K>(tb, ctx, lds, acc);
+      } else {
+        ta = tb;   // odd count: the tile in flight is the next row block's first
+      }
+    }
+    red[wave * 64 + lane] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
+    lane_group_barrier();
+    if (wave == 0) {
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < kLaneWaves; ++w) s += red[w * 64 + lane];
+      const int o = rb * 64 + lane;
+      if (o < job.out) as_global(job.y)[o] = __builtin_bit_cast(uint16_t, (_Float16)s);
+    }
+  }
+}
+
+template <int KA, int KB>
+__device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, int tid, char* lds) {
+  if (block >= job.nrq) return;
+  if constexpr (KA != KB) {
+    if (job.k_dev != nullptr && __builtin_amdgcn_readfirstlane(*as_global(job.k_dev)) == KB) {
+      gemv_lane<KB>(job, job.lut_off_b, block, tid, lds);
+      return;
+    }
+  }
+  gemv_lane<KA>(job, job.lut_off_a, block, tid, lds);
+}
+
+// jobs == nullptr: the job passed by value, for njobs right-hand sides, one after the other (sample s reads
+// x + s * in and writes y + s * out; workgroups [s * nblocks, (s + 1) * nblocks) serve it); else block b belongs
+// to the last job of the table whose block_start <= b
+template <int KA, int KB>
+__global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
+  __shared__ __attribute__((aligned(16))) char lds[lane_lds_bytes<KA, KB>()];
+  if (jobs == nullptr) {
+    const int sample = blockIdx.x / one.nblocks;
+    one.x += (size_t)sample * one.ncw * 32;
+    one.y += (size_t)sample * one.out;
+    gemv_lane_block<KA, KB>(one, blockIdx.x - sample * one.nblocks, threadIdx.x, lds);
+    return;
+  }
+  const int b = blockIdx.x;
+  int lo = 0, hi = njobs - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (jobs[mid].block_start <= b) lo = mid; else hi = mid - 1;
+  }
+  GemvJob job = jobs[lo];
+  gemv_lane_block<KA, KB>(job, b - job.block_start, threadIdx.x, lds);
+}
+
+}  // namespace dpllm

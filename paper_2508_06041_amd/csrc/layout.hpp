@@ -10,6 +10,11 @@
 //     adjacent positions q, q-1, ..., q-k+1 of planes 0..k-1, and whole code fields are
 //     assembled with mask-merge instructions and no per-plane shifts, for every k.
 // Rows are padded to a multiple of 4 with zero words; tables are padded with zero rows.
+//
+// A second arrangement of the same words (kLayoutRowLane) serves the row-per-lane GEMV: a plane is cut into
+// tiles of 64 rows x 128 columns; the tile stores, row after row, the four 32-column words of that row, so
+// lane l of a wavefront reads its own row's 16 bytes and the wavefront reads 1 KiB of contiguous memory.
+// Rows are padded to a multiple of 64, columns to a multiple of 128, with zero words.
 #pragma once
 #include <cstddef>
 #include <cstdint>
@@ -17,26 +22,38 @@
 namespace dpllm {
 
 constexpr size_t kAlign = 256;
+constexpr int kLayoutRowQuad = 0, kLayoutRowLane = 1;
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct LinearLayout {
   int out = 0, in = 0, p = 0, kmin = 0;
-  int nrq = 0;               // row quads = ceil(out / 4)
+  int mode = kLayoutRowQuad;
+  int nrq = 0;               // row groups: quads (ceil(out / 4)) or, row-per-lane, blocks of 64 rows
   int ncw = 0;               // 32-column words per row
+  int ncc = 0;               // row-per-lane: 128-column tiles per row
+  int rows_padded = 0;       // rows of the tables (zero rows appended)
   size_t plane_bytes = 0;    // stride between plane regions
   size_t lut_offset[9] = {}; // byte offset of the k-bit table, k = kmin..p
   size_t total_bytes = 0;
 
-  static LinearLayout make(int out, int in, int p, int kmin) {
+  static LinearLayout make(int out, int in, int p, int kmin, int mode = kLayoutRowQuad) {
     LinearLayout L;
-    L.out = out; L.in = in; L.p = p; L.kmin = kmin;
-    L.nrq = (out + 3) / 4;
+    L.out = out; L.in = in; L.p = p; L.kmin = kmin; L.mode = mode;
     L.ncw = in / 32;
-    L.plane_bytes = align_up((size_t)L.nrq * L.ncw * 16, kAlign);
+    L.ncc = (L.ncw + 3) / 4;
+    if (mode == kLayoutRowLane) {
+      L.nrq = (out + 63) / 64;
+      L.rows_padded = L.nrq * 64;
+      L.plane_bytes = (size_t)L.nrq * L.ncc * 1024;
+    } else {
+      L.nrq = (out + 3) / 4;
+      L.rows_padded = L.nrq * 4;
+      L.plane_bytes = align_up((size_t)L.nrq * L.ncw * 16, kAlign);
+    }
     size_t off = L.plane_bytes * p;
     for (int k = kmin; k <= p; ++k) {
       L.lut_offset[k] = off;
-      off += align_up((size_t)L.nrq * 4 * ((size_t)1 << k) * 2, kAlign);
+      off += align_up((size_t)L.rows_padded * ((size_t)1 << k) * 2, kAlign);
     }
     L.total_bytes = off;
     return L;
