@@ -209,10 +209,20 @@ GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, c
 
 // row quads one wavefront streams (workgroup b of a job takes row quads b, b + nblocks, ...): enough
 // wavefronts to fill the chip several times over, long enough runs to amortise the pipeline fill
-int pick_rq_per_block(int mode, long total_rq) {
-  // row-per-lane: the unit is a block of 64 rows and a workgroup of eight wavefronts streams it
-  long r = total_rq / (mode == kLayoutRowLane ? 2048 : 8192);
+int pick_rq_per_block(long total_rq) {
+  long r = total_rq / 8192;
   return (int)std::min<long>(8, std::max<long>(1, r));
+}
+
+// Row-per-lane arrangement: blocks of 64 rows one workgroup (eight wavefronts) streams.  A workgroup should
+// run for some tens of microseconds (about 384 KiB of planes): shorter ones pay their start-up (tables, first
+// loads) too often, longer ones leave the chip half empty at the end of the launch; and a launch wants at
+// least a few workgroups per compute unit.
+int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks) {
+  const long bytes_per_block = 64L * L.in * k / 8;
+  long r = std::min<long>(8, std::max<long>(1, 393216 / std::max<long>(1, bytes_per_block)));
+  while (r > 1 && total_blocks / r < 1024) --r;
+  return (int)r;
 }
 
 template <int B>
@@ -252,7 +262,7 @@ int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t
                 int B, hipStream_t st) {
   if (!has_fast_kernel(ka, kb)) return launch_plain(m, lin, ka, kb, k_dev, x, y, B, st);
   GemvJob j = make_gemv_job(lin, ka, kb, k_dev, x, y);
-  const int rpb = pick_rq_per_block(lin.L.mode, lin.L.nrq);
+  const int rpb = lin.L.mode == kLayoutRowLane ? pick_blocks_per_group(lin.L, kb, lin.L.nrq) : pick_rq_per_block(lin.L.nrq);
   j.nblocks = (lin.L.nrq + rpb - 1) / rpb;
   launch_fast(lin.L.mode, ka, kb, nullptr, B, j, j.nblocks * B, st);
   HIP_TRY(m, hipGetLastError());
@@ -334,13 +344,14 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       long total_rq = 0;
       for (int j = id; j < end; ++j)
         if (cls_of(j) == c) total_rq += m->linears[j].L.nrq;
-      const int rpb = pick_rq_per_block(c.mode, total_rq);
+      const int rpb_quad = pick_rq_per_block(total_rq);
       int blocks = 0;
       for (int j = id; j < end; ++j) {
         if (!(cls_of(j) == c)) continue;
         const Linear& lin = m->linears[j];
         const Selector& s = lin.sel[lin.active];
         GemvJob gj = make_gemv_job(lin, s.l, s.h, s.l == s.h ? nullptr : k_dev + j, xs[j], ys[j]);
+        const int rpb = c.mode == kLayoutRowLane ? pick_blocks_per_group(lin.L, s.h, total_rq) : rpb_quad;
         gj.nblocks = (lin.L.nrq + rpb - 1) / rpb;
         gj.block_start = blocks;
         blocks += gj.nblocks;

@@ -337,43 +337,48 @@ __device__ __forceinline__ void lane_group_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// tiles in registers per wavefront: one being decoded, the others in flight
+template <int K>
+constexpr int kLaneDepth = K == 3 ? 3 : 2;
+
 // One workgroup: row blocks block, block + nblocks, ... of a job; wavefront w takes the column tiles
-// [w ncc / 8, (w + 1) ncc / 8) of every row block.  Tile loads run one tile ahead, also across row blocks.
+// [w ncc / 8, (w + 1) ncc / 8) of every row block.  Tile loads run kLaneDepth - 1 tiles ahead, also across row
+// blocks; past the end of the run the ring is refilled with the last tile again (never decoded).
 template <int K>
 __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int tid, char* lds) {
+  constexpr int D = kLaneDepth<K>;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const LaneCtx ctx = lane_ctx(lane);
   float* red = reinterpret_cast<float*>(lds + LaneDecode<K>::table_bytes);
   const int c0 = wave * job.ncc / kLaneWaves, c1 = (wave + 1) * job.ncc / kLaneWaves;
   const int nrb = job.nrq;                     // row blocks of the job
+  const int step = job.nblocks;
   const DPLLM_GLOBAL uint16_t* lut_base = as_global(reinterpret_cast<const uint16_t*>(job.arena + lut_off));
   const bool ragged = (job.ncw & 3) != 0;
-  LaneTile<K> ta, tb;
+  const bool idle = c0 >= c1;                  // fewer tiles than wavefronts: this one only helps with the tables
+  LaneTile<K> ring[D];
   LaneLut<K> L;
   lane_fetch_lut<K>(L, lut_base, block, lane, wave);
-  if (c0 < c1) lane_load_tile<K>(ta, job, ctx, block, c0, lane);
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int rb = block; rb < nrb; rb += job.nblocks) {
-    lane_build_table<K>(L, wave, ctx.lanecol, lds);
-    const int rbn = rb + job.nblocks < nrb ? rb + job.nblocks : rb;
-    lane_fetch_lut<K>(L, lut_base, rbn, lane, wave);
-    lane_group_barrier();
-    for (int cc = c0; cc < c1; cc += 2) {
-      {  // tile in ta; the next one travels into tb
-        const bool more = cc + 1 < c1;
-        lane_load_tile<K>(tb, job, ctx, more ? rb : rbn, more ? cc + 1 : c0, lane);
-        if (ragged && cc == job.ncc - 1) lane_zero_tail<K>(ta, cc, job.ncw);
-        lane_compute<K>(ta, ctx, lds, acc);
-      }
-      if (cc + 1 < c1) {  // tile in tb; the next one travels into ta
-        const bool more = cc + 2 < c1;
-        lane_load_tile<K>(ta, job, ctx, more ? rb : rbn, more ? cc + 2 : c0, lane);
-        if (ragged && cc + 1 == job.ncc - 1) lane_zero_tail<K>(tb, cc + 1, job.ncw);
-        lane_compute<K>(tb, ctx, lds, acc);
-      } else {
-        ta = tb;   // odd count: the tile in flight is the next row block's first
-      }
+  int lrb = block, lcc = c0;                   // load cursor
+  auto load_next = [&](LaneTile<K>& t) {
+    lane_load_tile<K>(t, job, ctx, lrb, lcc, lane);
+    if (++lcc >= c1) {
+      lcc = c0;
+      if (lrb + step < nrb) lrb += step; else lcc = c1 - 1;   // end of the run: stay on the last tile
     }
+  };
+  if (!idle) {
+#pragma unroll
+    for (int i = 0; i < D - 1; ++i) load_next(ring[i]);
+  }
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  int rb = block, cc = c0;                     // compute cursor
+  auto open_block = [&]() {
+    lane_build_table<K>(L, wave, ctx.lanecol, lds);
+    lane_fetch_lut<K>(L, lut_base, rb + step < nrb ? rb + step : rb, lane, wave);
+    lane_group_barrier();
+  };
+  auto close_block = [&]() {
     red[wave * 64 + lane] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
     lane_group_barrier();
@@ -383,6 +388,30 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       for (int w = 0; w < kLaneWaves; ++w) s += red[w * 64 + lane];
       const int o = rb * 64 + lane;
       if (o < job.out) as_global(job.y)[o] = __builtin_bit_cast(uint16_t, (_Float16)s);
+    }
+  };
+  open_block();
+  if (idle) {
+    for (;;) {
+      close_block();
+      rb += step;
+      if (rb >= nrb) return;
+      open_block();
+    }
+  }
+  for (;;) {
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+      load_next(ring[(s + D - 1) % D]);
+      if (ragged && cc == job.ncc - 1) lane_zero_tail<K>(ring[s], cc, job.ncw);
+      lane_compute<K>(ring[s], ctx, lds, acc);
+      if (++cc >= c1) {
+        close_block();
+        rb += step;
+        if (rb >= nrb) return;
+        cc = c0;
+        open_block();
+      }
     }
   }
 }
