@@ -9,9 +9,10 @@
 // interleaved in LDS (entry e of row l at byte e * 256 + l * 4), so lane l only ever touches bank l mod 32 and
 // lookups are free of bank conflicts whatever the table size; the two-weight tables of k = 3 and k = 4, which
 // cost 4 - 6 LDS cycles per lookup when a whole wavefront shares one row's table, cost 2.
-// The activations are the same for all lanes.  A lane loads 16 bytes of them per word (lane l takes the
-// pairs 4 (l mod 4) .. + 3), and the multiply-add reads the pair it needs from the right lane of its quad with
-// a DPP quad broadcast: 16 registers hold the 64 activation pairs of a tile.
+// The activations are the same for all lanes.  With every tile a lane fetches one dword of them (256 bytes per
+// wavefront); before the tile is decoded the wavefront parks them in a private LDS slot and every lane reads
+// back 16 bytes per word (lane l takes the pairs 4 (l mod 4) .. + 3).  The multiply-add reads the pair it
+// needs from the right lane of its quad with a DPP quad broadcast: 16 registers hold the 64 pairs of a tile.
 // Each lane accumulates its own row: no cross-lane reduction.  A workgroup is eight wavefronts that split the
 // columns of the same 64 rows and share the tables; their eight partial sums per row meet in LDS.
 //
@@ -44,11 +45,15 @@ struct LaneDecode {
   __host__ __device__ static constexpr int rot(int c) { return (c + 1) & 7; }
   __host__ __device__ static constexpr int byte(int col) { return ((top(col) - rot(word(col))) & 31) >> 3; }
 };
+constexpr int kLaneRedBytes = kLaneWaves * 64 * 4;            // the partial sums of the eight wavefronts
+constexpr int kLaneXBytes = 512;                              // per wavefront: a tile's activations, natural and re-paired
 template <int KA, int KB>
-__host__ __device__ constexpr int lane_lds_bytes() {
+__host__ __device__ constexpr int lane_table_bytes() {
   constexpr int a = LaneDecode<KA>::table_bytes, b = LaneDecode<KB>::table_bytes;
-  return (a > b ? a : b) + kLaneWaves * 64 * 4;               // + the partial sums of the eight wavefronts
+  return a > b ? a : b;
 }
+template <int KA, int KB>
+__host__ __device__ constexpr int lane_lds_bytes() { return lane_table_bytes<KA, KB>() + kLaneRedBytes + kLaneWaves * kLaneXBytes; }
 
 // x pair held by lane Q of the quad, times the looked-up pair, added to acc
 template <int Q>
@@ -69,74 +74,44 @@ __device__ __forceinline__ uint32_t lane_entry_addr(uint32_t t, uint32_t lanecol
 
 __device__ __forceinline__ uint32_t lds_u32(const char* lds, uint32_t addr) { return *reinterpret_cast<const uint32_t*>(lds + addr); }
 
-// ---- a tile: the lane's row, 128 columns ------------------------------------------------------------------
-// x[j]: the lane's share of the activation pairs of word j.  k != 4: natural pairs (2i, 2i+1), lane q of a quad
-// holds i = 4 q .. 4 q + 3.  k = 4: the two 16-byte blocks the lane's four pairs (16 a + b: two columns 14 - 22
-// apart) are cut from, re-paired by lane_pair_x4 before use.
+// ---- a tile: the lane's row, 128 columns, and the lane's dword of the tile's 128 activations -------------------
 template <int K>
 struct LaneTile {
   u32x4 w[K];
-  u32x4 x[K == 4 ? 8 : 4];
+  uint32_t x;
 };
-
-struct LaneCtx {
-  uint32_t lanecol;     // lane * 4: the lane's column of the interleaved tables
-  int xa, xb;           // k = 4: 16-byte block numbers (inside a word's 64 bytes) of the lane's two activation blocks
-  uint32_t xsel;        // k = 4: byte selector that packs the wanted halves
-  bool xodd;            // k = 4: odd quad lanes take the second block rotated by one pair
-};
-
-__device__ __forceinline__ LaneCtx lane_ctx(int lane) {
-  LaneCtx c;
-  c.lanecol = (uint32_t)lane * 4;
-  const int q = lane & 3;
-  // quad lane q serves the pairs of merged word q (see nibble_pair_col_hi / _lo): upper-nibble columns come
-  // from natural pairs {8.., 4.., 12.., 0..}[q], lower-nibble columns from {0.., 12.., 4.., 8..}[q]
-  c.xa = q == 0 ? 2 : q == 1 ? 1 : q == 2 ? 3 : 0;
-  c.xb = q == 0 ? 0 : q == 1 ? 3 : q == 2 ? 1 : 2;
-  c.xodd = (q & 1) != 0;
-  c.xsel = c.xodd ? 0x05040100u : 0x07060302u;   // odd: the even columns (low halves); even: the odd columns
-  return c;
-}
 
 template <int K>
-__device__ __forceinline__ void lane_load_tile(LaneTile<K>& t, const GemvJob& job, const LaneCtx& ctx, int rb, int cc, int lane) {
+__device__ __forceinline__ void lane_load_tile(LaneTile<K>& t, const GemvJob& job, int rb, int cc, int lane) {
   const DPLLM_GLOBAL u32x4* p = as_global(reinterpret_cast<const u32x4*>(job.arena)) + ((size_t)rb * job.ncc + cc) * 64 + lane;
 #pragma unroll
   for (int b = 0; b < K; ++b) t.w[b] = load_stream(p + (size_t)b * job.plane_stride_u4);
-  const DPLLM_GLOBAL u32x4* xp = as_global(reinterpret_cast<const u32x4*>(job.x));
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int cw = min(cc * 4 + j, job.ncw - 1);   // words past the end of the row: clamped here, zeroed before use
-    if constexpr (K == 4) {
-      t.x[2 * j] = xp[(size_t)cw * 4 + ctx.xa];
-      t.x[2 * j + 1] = xp[(size_t)cw * 4 + ctx.xb];
-    } else {
-      t.x[j] = xp[(size_t)cw * 4 + (lane & 3)];
-    }
-  }
+  // columns past the end of a ragged row hold zero codes, whose centroid is not zero: their activations read as 0
+  const int c = cc * 128 + lane * 2, last = job.ncw * 32 - 2;
+  const uint32_t v = *reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(as_global(job.x) + min(c, last));
+  t.x = c <= last ? v : 0u;
 }
 
-// words past the end of a ragged row hold zero codes, whose centroid is not zero: their activations are zeroed
+// Parks the tile's activations in the wavefront's LDS slot and returns the lane's 16 bytes of every word:
+// xq[j][m] = pair 4 q + m of word j, q = lane mod 4.  k != 4: the natural pairs (2i, 2i+1).  k = 4: the pairs
+// (x[col_hi], x[col_lo]) of merged word q, byte m (see nibble_pair_col_hi / _lo), cut from the natural copy.
 template <int K>
-__device__ __forceinline__ void lane_zero_tail(LaneTile<K>& t, int cc, int ncw) {
+__device__ __forceinline__ void lane_park_x(uint32_t x, int lane, char* slot, u32x4 (&xq)[4]) {
+  *reinterpret_cast<uint32_t*>(slot + lane * 4) = x;
+  lds_order();
+  const char* src = slot;
+  if constexpr (K == 4) {
+    const int j = lane >> 4, q = (lane >> 2) & 3, m = lane & 3, mr = (m + 3) & 3;
+    const int ca = q == 0 ? 17 + 2 * m : q == 1 ? 8 + 2 * m : q == 2 ? 25 + 2 * m : 2 * m;
+    const int cb = q == 0 ? 1 + 2 * m : q == 1 ? 24 + 2 * mr : q == 2 ? 9 + 2 * m : 16 + 2 * mr;
+    const uint32_t lo = *reinterpret_cast<const uint16_t*>(slot + (j * 32 + ca) * 2);
+    const uint32_t hi = *reinterpret_cast<const uint16_t*>(slot + (j * 32 + cb) * 2);
+    *reinterpret_cast<uint32_t*>(slot + 256 + lane * 4) = lo | (hi << 16);
+    lds_order();
+    src = slot + 256;
+  }
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    if (cc * 4 + j >= ncw) {
-      if constexpr (K == 4) { t.x[2 * j] = u32x4{0u, 0u, 0u, 0u}; t.x[2 * j + 1] = u32x4{0u, 0u, 0u, 0u}; }
-      else t.x[j] = u32x4{0u, 0u, 0u, 0u};
-    }
-}
-
-// k = 4: pairs (x[col_hi], x[col_lo]) of merged word q = quad lane, byte m = register m
-__device__ __forceinline__ u32x4 lane_pair_x4(const u32x4& a, const u32x4& b, const LaneCtx& ctx) {
-  const uint32_t b0 = ctx.xodd ? b.w : b.x, b1 = ctx.xodd ? b.x : b.y, b2 = ctx.xodd ? b.y : b.z, b3 = ctx.xodd ? b.z : b.w;
-  u32x4 r;
-  r.x = __builtin_amdgcn_perm(b0, a.x, ctx.xsel);
-  r.y = __builtin_amdgcn_perm(b1, a.y, ctx.xsel);
-  r.z = __builtin_amdgcn_perm(b2, a.z, ctx.xsel);
-  r.w = __builtin_amdgcn_perm(b3, a.w, ctx.xsel);
-  return r;
+  for (int j = 0; j < 4; ++j) xq[j] = *reinterpret_cast<const u32x4*>(src + j * 64 + (lane & 3) * 16);
 }
 
 // ---- entry words of one 32-column word -----------------------------------------------------------------------
@@ -201,21 +176,20 @@ __device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], con
 // ---- one tile -------------------------------------------------------------------------------------------------
 // Lookups run in chunks of eight; the next chunk's lookups are issued before the current chunk's multiply-adds.
 template <int K>
-__device__ __forceinline__ void lane_compute(const LaneTile<K>& t, const LaneCtx& ctx, const char* lds, float (&acc)[4]) {
-  const uint32_t lanecol = ctx.lanecol;
+__device__ __forceinline__ void lane_compute(const LaneTile<K>& t, uint32_t lanecol, int lane, const char* lds, char* slot,
+                                             float (&acc)[4]) {
   uint32_t va[8], vb[8];
+  u32x4 xq[4];
+  lane_park_x<K>(t.x, lane, slot, xq);
   if constexpr (LaneDecode<K>::pair) {
     uint32_t T[4][4];
-    u32x4 xq[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if constexpr (K == 3) {
         lane_entries3(t.w[0][j], t.w[1][j], t.w[2][j], T[j]);
-        xq[j] = t.x[j];
       } else {
         const uint32_t w[4] = {t.w[0][j], t.w[1][j], t.w[2][j], t.w[3][j]};
         merge_nibble_pairs(w, T[j]);
-        xq[j] = lane_pair_x4(t.x[2 * j], t.x[2 * j + 1], ctx);
       }
     }
     lane_issue_pairs<0>(T[0], lanecol, lds, va);
@@ -249,19 +223,19 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K>& t, const LaneCtx
       }
       lane_issue_singles<K, 1>(R[j & 1], lanecol, lds, vb);
       sched_fence();
-      lane_consume_singles<0>(va, t.x[j], acc);
+      lane_consume_singles<0>(va, xq[j], acc);
       sched_fence();
       lane_issue_singles<K, 2>(R[j & 1], lanecol, lds, va);
       sched_fence();
-      lane_consume_singles<1>(vb, t.x[j], acc);
+      lane_consume_singles<1>(vb, xq[j], acc);
       sched_fence();
       lane_issue_singles<K, 3>(R[j & 1], lanecol, lds, vb);
       sched_fence();
-      lane_consume_singles<2>(va, t.x[j], acc);
+      lane_consume_singles<2>(va, xq[j], acc);
       sched_fence();
       if (j + 1 < 4) lane_issue_singles<K, 0>(R[(j + 1) & 1], lanecol, lds, va);
       sched_fence();
-      lane_consume_singles<3>(vb, t.x[j], acc);
+      lane_consume_singles<3>(vb, xq[j], acc);
       sched_fence();
     }
   }
@@ -339,29 +313,29 @@ __device__ __forceinline__ void lane_group_barrier() {
 
 // tiles in registers per wavefront: one being decoded, the others in flight
 template <int K>
-constexpr int kLaneDepth = K == 3 ? 3 : 2;
+constexpr int kLaneDepth = K <= 4 ? 3 : 2;
 
 // One workgroup: row blocks block, block + nblocks, ... of a job; wavefront w takes the column tiles
 // [w ncc / 8, (w + 1) ncc / 8) of every row block.  Tile loads run kLaneDepth - 1 tiles ahead, also across row
 // blocks; past the end of the run the ring is refilled with the last tile again (never decoded).
 template <int K>
-__device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int tid, char* lds) {
+__device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int tid, char* lds, int table_bytes) {
   constexpr int D = kLaneDepth<K>;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-  const LaneCtx ctx = lane_ctx(lane);
-  float* red = reinterpret_cast<float*>(lds + LaneDecode<K>::table_bytes);
+  const uint32_t lanecol = (uint32_t)lane * 4;  // the lane's column of the interleaved tables
+  float* red = reinterpret_cast<float*>(lds + table_bytes);
+  char* slot = lds + table_bytes + kLaneRedBytes + wave * kLaneXBytes;
   const int c0 = wave * job.ncc / kLaneWaves, c1 = (wave + 1) * job.ncc / kLaneWaves;
   const int nrb = job.nrq;                     // row blocks of the job
   const int step = job.nblocks;
   const DPLLM_GLOBAL uint16_t* lut_base = as_global(reinterpret_cast<const uint16_t*>(job.arena + lut_off));
-  const bool ragged = (job.ncw & 3) != 0;
   const bool idle = c0 >= c1;                  // fewer tiles than wavefronts: this one only helps with the tables
   LaneTile<K> ring[D];
   LaneLut<K> L;
   lane_fetch_lut<K>(L, lut_base, block, lane, wave);
   int lrb = block, lcc = c0;                   // load cursor
   auto load_next = [&](LaneTile<K>& t) {
-    lane_load_tile<K>(t, job, ctx, lrb, lcc, lane);
+    lane_load_tile<K>(t, job, lrb, lcc, lane);
     if (++lcc >= c1) {
       lcc = c0;
       if (lrb + step < nrb) lrb += step; else lcc = c1 - 1;   // end of the run: stay on the last tile
@@ -374,7 +348,7 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   int rb = block, cc = c0;                     // compute cursor
   auto open_block = [&]() {
-    lane_build_table<K>(L, wave, ctx.lanecol, lds);
+    lane_build_table<K>(L, wave, lanecol, lds);
     lane_fetch_lut<K>(L, lut_base, rb + step < nrb ? rb + step : rb, lane, wave);
     lane_group_barrier();
   };
@@ -403,8 +377,7 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
 #pragma unroll
     for (int s = 0; s < D; ++s) {
       load_next(ring[(s + D - 1) % D]);
-      if (ragged && cc == job.ncc - 1) lane_zero_tail<K>(ring[s], cc, job.ncw);
-      lane_compute<K>(ring[s], ctx, lds, acc);
+      lane_compute<K>(ring[s], lanecol, lane, lds, slot, acc);
       if (++cc >= c1) {
         close_block();
         rb += step;
@@ -419,13 +392,14 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
 template <int KA, int KB>
 __device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, int tid, char* lds) {
   if (block >= job.nrq) return;
+  constexpr int table_bytes = lane_table_bytes<KA, KB>();
   if constexpr (KA != KB) {
     if (job.k_dev != nullptr && __builtin_amdgcn_readfirstlane(*as_global(job.k_dev)) == KB) {
-      gemv_lane<KB>(job, job.lut_off_b, block, tid, lds);
+      gemv_lane<KB>(job, job.lut_off_b, block, tid, lds, table_bytes);
       return;
     }
   }
-  gemv_lane<KA>(job, job.lut_off_a, block, tid, lds);
+  gemv_lane<KA>(job, job.lut_off_a, block, tid, lds, table_bytes);
 }
 
 // jobs == nullptr: the job passed by value, for njobs right-hand sides, one after the other (sample s reads
@@ -433,6 +407,7 @@ __device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, i
 // to the last job of the table whose block_start <= b
 template <int KA, int KB>
 __global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
+  // the tables sit at LDS address 0, which the lookup addresses assume
   __shared__ __attribute__((aligned(16))) char lds[lane_lds_bytes<KA, KB>()];
   if (jobs == nullptr) {
     const int sample = blockIdx.x / one.nblocks;
