@@ -34,14 +34,14 @@ def selector_bytes(in_, r=RANK):
 
 
 def build_model(dp, synth, torch, shapes, n_blocks, p, l, h, n_x, seed=1234, keep_blocks=(0,), log=None,
-                quantile=None):
+                quantile=None, layout=None):
     """Loads n_blocks x len(shapes) linears generated on the GPU and attaches one projection selector each.
     Returns (model, meta) where meta carries shapes, thresholds, G, the activation sets and host copies of
     the linears of `keep_blocks` for the oracle.  Thresholds: tau ~ U[0.05, 0.3] times the median of
     ||W_h x|| (default), or the `quantile` of the calibration estimates."""
     import numpy as np
     n = n_blocks * len(shapes)
-    model = dp.Model(n)
+    model = dp.Model(n, layout=layout)
     ins = sorted({in_ for _, _, in_ in shapes})
     xs_by_in = {in_: synth.make_x(in_, n_x, seed=seed + in_, device="cuda") for in_ in ins}
     rng = np.random.default_rng(seed)
@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-k sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only (no HIP graph replay)")
+    ap.add_argument("--layout", choices=["rowlane", "rowquad"], default="rowlane",
+                    help="arrangement of the planes: one row per lane (default; fastest for a whole step) or four rows per lane")
     ap.add_argument("--copy-yardstick", action="store_true",
                     help="also run a plain 1 GiB copy kernel (for scaling hardware byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -109,7 +111,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     shapes, p, l, h, n_x = synth.LLAMA_7B, 8, 3, 4, 256
-    model, meta = build_model(dp, synth, torch, shapes, args.blocks, p, l, h, n_x, log=log)
+    layout = dp.DPLLM_LAYOUT_ROWLANE if args.layout == "rowlane" else dp.DPLLM_LAYOUT_ROWQUAD
+    model, meta = build_model(dp, synth, torch, shapes, args.blocks, p, l, h, n_x, log=log, layout=layout)
+    gemv_name = "gemv_lane_kernel<3,4>" if args.layout == "rowlane" else "gemv_kernel<3,4,1>"
     n = len(meta["shapes"])
     ins = sorted(meta["xs_by_in"])
     # the activation vectors of a step sit in one buffer (one copy per step); 128-byte aligned slices
@@ -262,7 +266,7 @@ def main():
         "config": {"workload": "Llama-7B-shaped decode step: %d blocks x 7 linears, p=8 bitplanes, (l,h)=(3,4), "
                                "rank-64 projection selectors, thresholds tau~U[0.05,0.3] x median||W_h x||, "
                                "256 outlier-fp16 activation vectors, batch 1" % args.blocks,
-                   "linears": n, "frac_of_hbm_peak": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+                   "linears": n, "layout": args.layout, "frac_of_hbm_peak": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "us_per_decode_step": round(ms_step * 1e3, 1),
         "us_per_decode_step_eager": round(ms_step_eager * 1e3, 1),
         "launch": launch_mode,
@@ -271,7 +275,7 @@ def main():
         "selector": {"us_per_step": round(ms_sel * 1e3, 1), "GBps": round(sel_bytes / (ms_sel * 1e-3) / 1e9, 1),
                      "share_of_step": round(ms_sel / (ms_sel + ms_gemv), 4)},
         "per_k": per_k,
-        "roofline": {"bound": "hbm", "kernel": "gemv_kernel<3,4,1>", "achieved": round(roof_achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": gemv_name, "achieved": round(roof_achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(roof_achieved / HBM_PEAK_GBPS, 4),
                      "us_per_launch": round(ms_gemv * 1e3, 1), "algorithmic_bytes": int(gemv_bytes0),
                      "measured_read_ceiling": round(read_ceiling, 1),

@@ -16,11 +16,19 @@ REL_L2 = 2e-3
 DECISION_BAND = 1e-9
 
 
-@pytest.fixture(scope="module")
-def dp():
+@pytest.fixture(scope="module", params=["rowquad", "rowlane"])
+def dp(request):
+    """The binding, with every model of the test created in one of the two plane arrangements."""
+    import os
     import paper_2508_06041_amd as dp
     assert torch.cuda.is_available()
-    return dp
+    old = os.environ.get("DPLLM_LAYOUT")
+    os.environ["DPLLM_LAYOUT"] = request.param
+    yield dp
+    if old is None:
+        del os.environ["DPLLM_LAYOUT"]
+    else:
+        os.environ["DPLLM_LAYOUT"] = old
 
 
 def rel_l2(got, ref):
