@@ -115,25 +115,34 @@ __device__ __forceinline__ void lane_park_x(uint32_t x, int lane, char* slot, u3
 }
 
 // ---- entry words of one 32-column word -----------------------------------------------------------------------
-// k = 3: four words of four bytes (8 a + b), the pairs (2i, 2i+1), i = 4 jj + n
+// k = 3: four words of four bytes (8 a + b), the pairs (2i, 2i+1), i = 4 jj + n (word 3 is left rotated by
+// one byte: its pair n sits in byte n + 1)
 __device__ __forceinline__ void lane_entries3(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t (&T)[4]) {
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj) {
     const uint32_t m0 = rotl_c(0x90909090u, 2 * jj), m1 = rotl_c(0x48484848u, 2 * jj), m2 = rotl_c(0x24242424u, 2 * jj);
-    T[jj] = __builtin_rotateright32(bfi_insn(m0, w0, bfi_insn(m1, w1, w2 & m2)), 2 * jj + 2);
+    const uint32_t o = bfi_insn(m0, w0, bfi_insn(m1, w1, w2 & m2));
+    T[jj] = jj == 3 ? o : __builtin_rotateright32(o, 2 * jj + 2);   // jj = 3: a whole byte, taken care of by the byte index
   }
 }
 
-// two-weight schemes: eight lookups from entry words JA, JA + 1
-template <int JA>
+// two-weight schemes: eight lookups from entry words JA, JA + 1 (S: byte shift of word 3, see lane_entries3)
+template <int JA, int S>
 __device__ __forceinline__ void lane_issue_pairs(const uint32_t (&T)[4], uint32_t lanecol, const char* lds, uint32_t (&v)[8]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint32_t t = T[JA + h];
-    v[4 * h + 0] = lds_u32(lds, lane_entry_addr<0>(t, lanecol));
-    v[4 * h + 1] = lds_u32(lds, lane_entry_addr<1>(t, lanecol));
-    v[4 * h + 2] = lds_u32(lds, lane_entry_addr<2>(t, lanecol));
-    v[4 * h + 3] = lds_u32(lds, lane_entry_addr<3>(t, lanecol));
+    if (JA + h == 3 && S == 1) {
+      v[4 * h + 0] = lds_u32(lds, lane_entry_addr<1>(t, lanecol));
+      v[4 * h + 1] = lds_u32(lds, lane_entry_addr<2>(t, lanecol));
+      v[4 * h + 2] = lds_u32(lds, lane_entry_addr<3>(t, lanecol));
+      v[4 * h + 3] = lds_u32(lds, lane_entry_addr<0>(t, lanecol));
+    } else {
+      v[4 * h + 0] = lds_u32(lds, lane_entry_addr<0>(t, lanecol));
+      v[4 * h + 1] = lds_u32(lds, lane_entry_addr<1>(t, lanecol));
+      v[4 * h + 2] = lds_u32(lds, lane_entry_addr<2>(t, lanecol));
+      v[4 * h + 3] = lds_u32(lds, lane_entry_addr<3>(t, lanecol));
+    }
   }
 }
 
@@ -192,14 +201,14 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K>& t, uint32_t lane
         merge_nibble_pairs(w, T[j]);
       }
     }
-    lane_issue_pairs<0>(T[0], lanecol, lds, va);
+    lane_issue_pairs<0, K == 3>(T[0], lanecol, lds, va);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      lane_issue_pairs<2>(T[j], lanecol, lds, vb);
+      lane_issue_pairs<2, K == 3>(T[j], lanecol, lds, vb);
       sched_fence();
       lane_consume_pairs<0>(va, xq[j], acc);
       sched_fence();
-      if (j + 1 < 4) lane_issue_pairs<0>(T[j + 1], lanecol, lds, va);
+      if (j + 1 < 4) lane_issue_pairs<0, K == 3>(T[j + 1], lanecol, lds, va);
       sched_fence();
       lane_consume_pairs<2>(vb, xq[j], acc);
       sched_fence();
@@ -330,9 +339,12 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   const int step = job.nblocks;
   const DPLLM_GLOBAL uint16_t* lut_base = as_global(reinterpret_cast<const uint16_t*>(job.arena + lut_off));
   const bool idle = c0 >= c1;                  // fewer tiles than wavefronts: this one only helps with the tables
+  // the table rows of the next row block travel one block ahead, except at k >= 7, where their 8 - 16 registers
+  // would cost the second workgroup per compute unit
+  constexpr bool kLutAhead = K <= 6;
   LaneTile<K> ring[D];
   LaneLut<K> L;
-  lane_fetch_lut<K>(L, lut_base, block, lane, wave);
+  if constexpr (kLutAhead) lane_fetch_lut<K>(L, lut_base, block, lane, wave);
   int lrb = block, lcc = c0;                   // load cursor
   auto load_next = [&](LaneTile<K>& t) {
     lane_load_tile<K>(t, job, lrb, lcc, lane);
@@ -348,8 +360,9 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   int rb = block, cc = c0;                     // compute cursor
   auto open_block = [&]() {
+    if constexpr (!kLutAhead) lane_fetch_lut<K>(L, lut_base, rb, lane, wave);
     lane_build_table<K>(L, wave, lanecol, lds);
-    lane_fetch_lut<K>(L, lut_base, rb + step < nrb ? rb + step : rb, lane, wave);
+    if constexpr (kLutAhead) lane_fetch_lut<K>(L, lut_base, rb + step < nrb ? rb + step : rb, lane, wave);
     lane_group_barrier();
   };
   auto close_block = [&]() {
