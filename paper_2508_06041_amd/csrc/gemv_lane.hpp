@@ -11,7 +11,8 @@
 // cost 4 - 6 LDS cycles per lookup when a whole wavefront shares one row's table, cost 2.
 // The activations are the same for all lanes.  With every tile a lane fetches one dword of them (256 bytes per
 // wavefront); before the tile is decoded the wavefront parks them in a private LDS slot and every lane reads
-// back 16 bytes per word (lane l takes the pairs 4 (l mod 4) .. + 3).  The multiply-add reads the pair it
+// back 16 bytes per word (lane l takes the pairs 4 (l mod 4) .. + 3).  A wavefront with at most four tiles per
+// row block (rows up to 4096 columns) parks them once for its whole run instead.  The multiply-add reads the pair it
 // needs from the right lane of its quad with a DPP quad broadcast: 16 registers hold the 64 pairs of a tile.
 // Each lane accumulates its own row: no cross-lane reduction.  A workgroup is eight wavefronts that split the
 // columns of the same 64 rows and share the tables; their eight partial sums per row meet in LDS.
@@ -46,7 +47,8 @@ struct LaneDecode {
   __host__ __device__ static constexpr int byte(int col) { return ((top(col) - rot(word(col))) & 31) >> 3; }
 };
 constexpr int kLaneRedBytes = kLaneWaves * 64 * 4;            // the partial sums of the eight wavefronts
-constexpr int kLaneXBytes = 512;                              // per wavefront: a tile's activations, natural and re-paired
+constexpr int kLaneKeepTiles = 4;                             // a wavefront with so few tiles per row block keeps their activations in LDS
+constexpr int kLaneXBytes = 512 + kLaneKeepTiles * 256;       // per wavefront: a tile's activations (natural, ready), kept tiles
 template <int KA, int KB>
 __host__ __device__ constexpr int lane_table_bytes() {
   constexpr int a = LaneDecode<KA>::table_bytes, b = LaneDecode<KB>::table_bytes;
@@ -81,37 +83,46 @@ struct LaneTile {
   uint32_t x;
 };
 
-template <int K>
-__device__ __forceinline__ void lane_load_tile(LaneTile<K>& t, const GemvJob& job, int rb, int cc, int lane) {
-  const DPLLM_GLOBAL u32x4* p = as_global(reinterpret_cast<const u32x4*>(job.arena)) + ((size_t)rb * job.ncc + cc) * 64 + lane;
-#pragma unroll
-  for (int b = 0; b < K; ++b) t.w[b] = load_stream(p + (size_t)b * job.plane_stride_u4);
-  // columns past the end of a ragged row hold zero codes, whose centroid is not zero: their activations read as 0
+// the lane's dword of the 128 activations of tile cc; columns past the end of a ragged row hold zero codes,
+// whose centroid is not zero: their activations read as 0
+__device__ __forceinline__ uint32_t lane_load_x(const GemvJob& job, int cc, int lane) {
   const int c = cc * 128 + lane * 2, last = job.ncw * 32 - 2;
   const uint32_t v = *reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(as_global(job.x) + min(c, last));
-  t.x = c <= last ? v : 0u;
+  return c <= last ? v : 0u;
 }
 
-// Parks the tile's activations in the wavefront's LDS slot and returns the lane's 16 bytes of every word:
-// xq[j][m] = pair 4 q + m of word j, q = lane mod 4.  k != 4: the natural pairs (2i, 2i+1).  k = 4: the pairs
-// (x[col_hi], x[col_lo]) of merged word q, byte m (see nibble_pair_col_hi / _lo), cut from the natural copy.
+// Loads are never predicated, which keeps the compiler's outstanding-load counts exact.  `real` = false (ring
+// slots past the end of the run): the K loads still issue, but all from the first 16 bytes of the activation
+// vector, which is hot in L2, so they cost no HBM traffic; the values are never decoded.
 template <int K>
-__device__ __forceinline__ void lane_park_x(uint32_t x, int lane, char* slot, u32x4 (&xq)[4]) {
-  *reinterpret_cast<uint32_t*>(slot + lane * 4) = x;
-  lds_order();
-  const char* src = slot;
+__device__ __forceinline__ void lane_load_tile(LaneTile<K>& t, const GemvJob& job, int rb, int cc, int lane, bool with_x, bool real) {
+  const DPLLM_GLOBAL u32x4* planes = as_global(reinterpret_cast<const u32x4*>(job.arena)) + ((size_t)rb * job.ncc + cc) * 64 + lane;
+  const DPLLM_GLOBAL u32x4* p = real ? planes : as_global(reinterpret_cast<const u32x4*>(job.x));
+  const size_t stride = real ? (size_t)job.plane_stride_u4 : 0;
+#pragma unroll
+  for (int b = 0; b < K; ++b) t.w[b] = load_stream(p + (size_t)b * stride);
+  if (with_x) t.x = lane_load_x(job, cc, lane);
+}
+
+// Parks a tile's activations in LDS in the form the lanes read back: 64 dwords, dword 16 j + 4 q + m = pair
+// 4 q + m of word j.  k != 4: the natural pairs (2i, 2i+1), so the lane's dword goes straight to `ready`.
+// k = 4: the pairs (x[col_hi], x[col_lo]) of merged word q, byte m (see nibble_pair_col_hi / _lo), cut from a
+// natural copy in `scratch`.
+template <int K>
+__device__ __forceinline__ void lane_park_x(uint32_t x, int lane, char* scratch, char* ready) {
   if constexpr (K == 4) {
+    *reinterpret_cast<uint32_t*>(scratch + lane * 4) = x;
+    lds_order();
     const int j = lane >> 4, q = (lane >> 2) & 3, m = lane & 3, mr = (m + 3) & 3;
     const int ca = q == 0 ? 17 + 2 * m : q == 1 ? 8 + 2 * m : q == 2 ? 25 + 2 * m : 2 * m;
     const int cb = q == 0 ? 1 + 2 * m : q == 1 ? 24 + 2 * mr : q == 2 ? 9 + 2 * m : 16 + 2 * mr;
-    const uint32_t lo = *reinterpret_cast<const uint16_t*>(slot + (j * 32 + ca) * 2);
-    const uint32_t hi = *reinterpret_cast<const uint16_t*>(slot + (j * 32 + cb) * 2);
-    *reinterpret_cast<uint32_t*>(slot + 256 + lane * 4) = lo | (hi << 16);
-    lds_order();
-    src = slot + 256;
+    const uint32_t lo = *reinterpret_cast<const uint16_t*>(scratch + (j * 32 + ca) * 2);
+    const uint32_t hi = *reinterpret_cast<const uint16_t*>(scratch + (j * 32 + cb) * 2);
+    *reinterpret_cast<uint32_t*>(ready + lane * 4) = lo | (hi << 16);
+  } else {
+    *reinterpret_cast<uint32_t*>(ready + lane * 4) = x;
   }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) xq[j] = *reinterpret_cast<const u32x4*>(src + j * 64 + (lane & 3) * 16);
+  lds_order();
 }
 
 // ---- entry words of one 32-column word -----------------------------------------------------------------------
@@ -185,11 +196,12 @@ __device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], con
 // ---- one tile -------------------------------------------------------------------------------------------------
 // Lookups run in chunks of eight; the next chunk's lookups are issued before the current chunk's multiply-adds.
 template <int K>
-__device__ __forceinline__ void lane_compute(const LaneTile<K>& t, uint32_t lanecol, int lane, const char* lds, char* slot,
+__device__ __forceinline__ void lane_compute(const LaneTile<K>& t, uint32_t lanecol, int lane, const char* lds, const char* xready,
                                              float (&acc)[4]) {
   uint32_t va[8], vb[8];
-  u32x4 xq[4];
-  lane_park_x<K>(t.x, lane, slot, xq);
+  u32x4 xq[4];   // xq[j][m] = pair 4 q + m of word j, q = lane mod 4
+#pragma unroll
+  for (int j = 0; j < 4; ++j) xq[j] = *reinterpret_cast<const u32x4*>(xready + j * 64 + (lane & 3) * 16);
   if constexpr (LaneDecode<K>::pair) {
     uint32_t T[4][4];
 #pragma unroll
@@ -326,7 +338,7 @@ constexpr int kLaneDepth = K <= 4 ? 3 : 2;
 
 // One workgroup: row blocks block, block + nblocks, ... of a job; wavefront w takes the column tiles
 // [w ncc / 8, (w + 1) ncc / 8) of every row block.  Tile loads run kLaneDepth - 1 tiles ahead, also across row
-// blocks; past the end of the run the ring is refilled with the last tile again (never decoded).
+// blocks; past the end of the run the ring is refilled with dummy loads (see lane_load_tile).
 template <int K>
 __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int tid, char* lds, int table_bytes) {
   constexpr int D = kLaneDepth<K>;
@@ -346,11 +358,18 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   LaneLut<K> L;
   if constexpr (kLutAhead) lane_fetch_lut<K>(L, lut_base, block, lane, wave);
   int lrb = block, lcc = c0;                   // load cursor
+  // few tiles per row block: their activations are parked once, for every row block of the run
+  const bool keep = c1 - c0 <= kLaneKeepTiles;
+  char* kept = slot + 512;
+  if (keep) {
+    for (int cc = c0; cc < c1; ++cc) lane_park_x<K>(lane_load_x(job, cc, lane), lane, slot, kept + (cc - c0) * 256);
+  }
+  bool more = true;                            // the load cursor is still inside the run
   auto load_next = [&](LaneTile<K>& t) {
-    lane_load_tile<K>(t, job, lrb, lcc, lane);
+    lane_load_tile<K>(t, job, lrb, lcc, lane, !keep, more);
     if (++lcc >= c1) {
       lcc = c0;
-      if (lrb + step < nrb) lrb += step; else lcc = c1 - 1;   // end of the run: stay on the last tile
+      if (lrb + step < nrb) lrb += step; else more = false;
     }
   };
   if (!idle) {
@@ -390,7 +409,12 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
 #pragma unroll
     for (int s = 0; s < D; ++s) {
       load_next(ring[(s + D - 1) % D]);
-      lane_compute<K>(ring[s], lanecol, lane, lds, slot, acc);
+      const char* xready = kept + (cc - c0) * 256;
+      if (!keep) {
+        lane_park_x<K>(ring[s].x, lane, slot, slot + 256);
+        xready = slot + 256;
+      }
+      lane_compute<K>(ring[s], lanecol, lane, lds, xready, acc);
       if (++cc >= c1) {
         close_block();
         rb += step;
