@@ -169,11 +169,15 @@ void launch_fast_t(const GemvJob* d_jobs, int njobs, const GemvJob& one, int blo
   }
 }
 
-// row-per-lane arrangement: a batch runs one sample after the other inside the launch
+// row-per-lane arrangement: a batch runs in groups of two samples that share one pass over the planes
 template <int KA, int KB>
 void launch_lane_t(const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
-  const int grid = d_jobs == nullptr ? one.nblocks * njobs : blocks;
-  hipLaunchKernelGGL((gemv_lane_kernel<KA, KB>), dim3(grid), dim3(kLaneThreads), 0, st, d_jobs, njobs, one);
+  if (d_jobs == nullptr && njobs > 1)
+    hipLaunchKernelGGL((gemv_lane_kernel<KA, KB, 2>), dim3(one.nblocks * ((njobs + 1) / 2)), dim3(kLaneThreads), 0, st, d_jobs,
+                       njobs, one);
+  else
+    hipLaunchKernelGGL((gemv_lane_kernel<KA, KB, 1>), dim3(d_jobs == nullptr ? one.nblocks : blocks), dim3(kLaneThreads), 0, st,
+                       d_jobs, njobs, one);
 }
 
 void launch_fast(int mode, int ka, int kb, const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {

@@ -16,6 +16,7 @@
 // needs from the right lane of its quad with a DPP quad broadcast: 16 registers hold the 64 pairs of a tile.
 // Each lane accumulates its own row: no cross-lane reduction.  A workgroup is eight wavefronts that split the
 // columns of the same 64 rows and share the tables; their eight partial sums per row meet in LDS.
+// Two right-hand sides can share a pass: every lookup then feeds two multiply-adds.
 //
 //   k = 3, 4 : two weights per lookup, tables of 64 / 256 fp16 pairs per row (16 / 64 KiB per workgroup)
 //   k >= 5   : one weight per lookup (table of 2^k entries per row, 8 .. 64 KiB), two results packed for one
@@ -54,8 +55,14 @@ __host__ __device__ constexpr int lane_table_bytes() {
   constexpr int a = LaneDecode<KA>::table_bytes, b = LaneDecode<KB>::table_bytes;
   return a > b ? a : b;
 }
-template <int KA, int KB>
-__host__ __device__ constexpr int lane_lds_bytes() { return lane_table_bytes<KA, KB>() + kLaneRedBytes + kLaneWaves * kLaneXBytes; }
+// NB right-hand sides per pass (1 or 2): NB sets of partial sums; with two, every sample has a 512-byte slot per
+// wavefront and nothing is kept across row blocks
+template <int NB>
+__host__ __device__ constexpr int lane_x_bytes() { return NB == 1 ? kLaneXBytes : NB * 512; }
+template <int KA, int KB, int NB>
+__host__ __device__ constexpr int lane_lds_bytes() {
+  return lane_table_bytes<KA, KB>() + NB * kLaneRedBytes + kLaneWaves * lane_x_bytes<NB>();
+}
 
 // x pair held by lane Q of the quad, times the looked-up pair, added to acc
 template <int Q>
@@ -77,31 +84,35 @@ __device__ __forceinline__ uint32_t lane_entry_addr(uint32_t t, uint32_t lanecol
 __device__ __forceinline__ uint32_t lds_u32(const char* lds, uint32_t addr) { return *reinterpret_cast<const uint32_t*>(lds + addr); }
 
 // ---- a tile: the lane's row, 128 columns, and the lane's dword of the tile's 128 activations -------------------
-template <int K>
+template <int K, int NB>
 struct LaneTile {
   u32x4 w[K];
-  uint32_t x;
+  uint32_t x[NB];
 };
 
 // the lane's dword of the 128 activations of tile cc; columns past the end of a ragged row hold zero codes,
 // whose centroid is not zero: their activations read as 0
-__device__ __forceinline__ uint32_t lane_load_x(const GemvJob& job, int cc, int lane) {
+__device__ __forceinline__ uint32_t lane_load_x(const GemvJob& job, int cc, int lane, int sample = 0) {
   const int c = cc * 128 + lane * 2, last = job.ncw * 32 - 2;
-  const uint32_t v = *reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(as_global(job.x) + min(c, last));
+  const uint32_t v = *reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(as_global(job.x) + (size_t)sample * job.ncw * 32 + min(c, last));
   return c <= last ? v : 0u;
 }
 
 // Loads are never predicated, which keeps the compiler's outstanding-load counts exact.  `real` = false (ring
 // slots past the end of the run): the K loads still issue, but all from the first 16 bytes of the activation
 // vector, which is hot in L2, so they cost no HBM traffic; the values are never decoded.
-template <int K>
-__device__ __forceinline__ void lane_load_tile(LaneTile<K>& t, const GemvJob& job, int rb, int cc, int lane, bool with_x, bool real) {
+template <int K, int NB>
+__device__ __forceinline__ void lane_load_tile(LaneTile<K, NB>& t, const GemvJob& job, int rb, int cc, int lane, bool with_x, bool real) {
   const DPLLM_GLOBAL u32x4* planes = as_global(reinterpret_cast<const u32x4*>(job.arena)) + ((size_t)rb * job.ncc + cc) * 64 + lane;
   const DPLLM_GLOBAL u32x4* p = real ? planes : as_global(reinterpret_cast<const u32x4*>(job.x));
   const size_t stride = real ? (size_t)job.plane_stride_u4 : 0;
 #pragma unroll
   for (int b = 0; b < K; ++b) t.w[b] = load_stream(p + (size_t)b * stride);
-  if (with_x) t.x = lane_load_x(job, cc, lane);
+  if (with_x) {
+    // a group with fewer than NB samples re-reads its last one (the sums are not stored)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) t.x[b] = lane_load_x(job, cc, lane, NB == 1 ? 0 : min(b, job.nsamples - 1));
+  }
 }
 
 // Parks a tile's activations in LDS in the form the lanes read back: 64 dwords, dword 16 j + 4 q + m = pair
@@ -195,13 +206,16 @@ __device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], con
 
 // ---- one tile -------------------------------------------------------------------------------------------------
 // Lookups run in chunks of eight; the next chunk's lookups are issued before the current chunk's multiply-adds.
-template <int K>
-__device__ __forceinline__ void lane_compute(const LaneTile<K>& t, uint32_t lanecol, int lane, const char* lds, const char* xready,
-                                             float (&acc)[4]) {
+// xready: the parked activations of sample 0; sample b at + b * xstep
+template <int K, int NB>
+__device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t lanecol, int lane, const char* lds, const char* xready,
+                                             int xstep, float (&acc)[NB][4]) {
   uint32_t va[8], vb[8];
-  u32x4 xq[4];   // xq[j][m] = pair 4 q + m of word j, q = lane mod 4
+  u32x4 xq[NB][4];   // xq[b][j][m] = pair 4 q + m of word j of sample b, q = lane mod 4
 #pragma unroll
-  for (int j = 0; j < 4; ++j) xq[j] = *reinterpret_cast<const u32x4*>(xready + j * 64 + (lane & 3) * 16);
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) xq[b][j] = *reinterpret_cast<const u32x4*>(xready + b * xstep + j * 64 + (lane & 3) * 16);
   if constexpr (LaneDecode<K>::pair) {
     uint32_t T[4][4];
 #pragma unroll
@@ -218,11 +232,17 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K>& t, uint32_t lane
     for (int j = 0; j < 4; ++j) {
       lane_issue_pairs<2, K == 3>(T[j], lanecol, lds, vb);
       sched_fence();
-      lane_consume_pairs<0>(va, xq[j], acc);
+      {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) lane_consume_pairs<0>(va, xq[b][j], acc[b]);
+      }
       sched_fence();
       if (j + 1 < 4) lane_issue_pairs<0, K == 3>(T[j + 1], lanecol, lds, va);
       sched_fence();
-      lane_consume_pairs<2>(vb, xq[j], acc);
+      {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) lane_consume_pairs<2>(vb, xq[b][j], acc[b]);
+      }
       sched_fence();
     }
   } else {
@@ -244,19 +264,31 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K>& t, uint32_t lane
       }
       lane_issue_singles<K, 1>(R[j & 1], lanecol, lds, vb);
       sched_fence();
-      lane_consume_singles<0>(va, xq[j], acc);
+      {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) lane_consume_singles<0>(va, xq[b][j], acc[b]);
+      }
       sched_fence();
       lane_issue_singles<K, 2>(R[j & 1], lanecol, lds, va);
       sched_fence();
-      lane_consume_singles<1>(vb, xq[j], acc);
+      {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) lane_consume_singles<1>(vb, xq[b][j], acc[b]);
+      }
       sched_fence();
       lane_issue_singles<K, 3>(R[j & 1], lanecol, lds, vb);
       sched_fence();
-      lane_consume_singles<2>(va, xq[j], acc);
+      {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) lane_consume_singles<2>(va, xq[b][j], acc[b]);
+      }
       sched_fence();
       if (j + 1 < 4) lane_issue_singles<K, 0>(R[(j + 1) & 1], lanecol, lds, va);
       sched_fence();
-      lane_consume_singles<3>(vb, xq[j], acc);
+      {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) lane_consume_singles<3>(vb, xq[b][j], acc[b]);
+      }
       sched_fence();
     }
   }
@@ -333,19 +365,19 @@ __device__ __forceinline__ void lane_group_barrier() {
 }
 
 // tiles in registers per wavefront: one being decoded, the others in flight
-template <int K>
-constexpr int kLaneDepth = K <= 4 ? 3 : 2;
+template <int K, int NB>
+constexpr int kLaneDepth = (K <= 4 && NB == 1) ? 3 : 2;
 
 // One workgroup: row blocks block, block + nblocks, ... of a job; wavefront w takes the column tiles
 // [w ncc / 8, (w + 1) ncc / 8) of every row block.  Tile loads run kLaneDepth - 1 tiles ahead, also across row
 // blocks; past the end of the run the ring is refilled with dummy loads (see lane_load_tile).
-template <int K>
+template <int K, int NB>
 __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int tid, char* lds, int table_bytes) {
-  constexpr int D = kLaneDepth<K>;
+  constexpr int D = kLaneDepth<K, NB>;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const uint32_t lanecol = (uint32_t)lane * 4;  // the lane's column of the interleaved tables
   float* red = reinterpret_cast<float*>(lds + table_bytes);
-  char* slot = lds + table_bytes + kLaneRedBytes + wave * kLaneXBytes;
+  char* slot = lds + table_bytes + NB * kLaneRedBytes + wave * lane_x_bytes<NB>();
   const int c0 = wave * job.ncc / kLaneWaves, c1 = (wave + 1) * job.ncc / kLaneWaves;
   const int nrb = job.nrq;                     // row blocks of the job
   const int step = job.nblocks;
@@ -354,19 +386,19 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   // the table rows of the next row block travel one block ahead, except at k >= 7, where their 8 - 16 registers
   // would cost the second workgroup per compute unit
   constexpr bool kLutAhead = K <= 6;
-  LaneTile<K> ring[D];
+  LaneTile<K, NB> ring[D];
   LaneLut<K> L;
   if constexpr (kLutAhead) lane_fetch_lut<K>(L, lut_base, block, lane, wave);
   int lrb = block, lcc = c0;                   // load cursor
   // few tiles per row block: their activations are parked once, for every row block of the run
-  const bool keep = c1 - c0 <= kLaneKeepTiles;
+  const bool keep = NB == 1 && c1 - c0 <= kLaneKeepTiles;
   char* kept = slot + 512;
   if (keep) {
     for (int cc = c0; cc < c1; ++cc) lane_park_x<K>(lane_load_x(job, cc, lane), lane, slot, kept + (cc - c0) * 256);
   }
   bool more = true;                            // the load cursor is still inside the run
-  auto load_next = [&](LaneTile<K>& t) {
-    lane_load_tile<K>(t, job, lrb, lcc, lane, !keep, more);
+  auto load_next = [&](LaneTile<K, NB>& t) {
+    lane_load_tile<K, NB>(t, job, lrb, lcc, lane, !keep, more);
     if (++lcc >= c1) {
       lcc = c0;
       if (lrb + step < nrb) lrb += step; else more = false;
@@ -376,7 +408,9 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
 #pragma unroll
     for (int i = 0; i < D - 1; ++i) load_next(ring[i]);
   }
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  float acc[NB][4];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) acc[b][0] = acc[b][1] = acc[b][2] = acc[b][3] = 0.f;
   int rb = block, cc = c0;                     // compute cursor
   auto open_block = [&]() {
     if constexpr (!kLutAhead) lane_fetch_lut<K>(L, lut_base, rb, lane, wave);
@@ -385,15 +419,18 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
     lane_group_barrier();
   };
   auto close_block = [&]() {
-    red[wave * 64 + lane] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      red[(b * kLaneWaves + wave) * 64 + lane] = (acc[b][0] + acc[b][1]) + (acc[b][2] + acc[b][3]);
+      acc[b][0] = acc[b][1] = acc[b][2] = acc[b][3] = 0.f;
+    }
     lane_group_barrier();
-    if (wave == 0) {
+    if (wave < NB && (NB == 1 || wave < job.nsamples)) {   // wavefront b stores sample b
       float s = 0.f;
 #pragma unroll
-      for (int w = 0; w < kLaneWaves; ++w) s += red[w * 64 + lane];
+      for (int w = 0; w < kLaneWaves; ++w) s += red[(wave * kLaneWaves + w) * 64 + lane];
       const int o = rb * 64 + lane;
-      if (o < job.out) as_global(job.y)[o] = __builtin_bit_cast(uint16_t, (_Float16)s);
+      if (o < job.out) as_global(job.y)[(size_t)wave * job.out + o] = __builtin_bit_cast(uint16_t, (_Float16)s);
     }
   };
   open_block();
@@ -411,10 +448,11 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       load_next(ring[(s + D - 1) % D]);
       const char* xready = kept + (cc - c0) * 256;
       if (!keep) {
-        lane_park_x<K>(ring[s].x, lane, slot, slot + 256);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) lane_park_x<K>(ring[s].x[b], lane, slot + b * 512, slot + b * 512 + 256);
         xready = slot + 256;
       }
-      lane_compute<K>(ring[s], lanecol, lane, lds, xready, acc);
+      lane_compute<K, NB>(ring[s], lanecol, lane, lds, xready, 512, acc);
       if (++cc >= c1) {
         close_block();
         rb += step;
@@ -426,41 +464,44 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   }
 }
 
-template <int KA, int KB>
+template <int KA, int KB, int NB>
 __device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, int tid, char* lds) {
   if (block >= job.nrq) return;
   constexpr int table_bytes = lane_table_bytes<KA, KB>();
   if constexpr (KA != KB) {
     if (job.k_dev != nullptr && __builtin_amdgcn_readfirstlane(*as_global(job.k_dev)) == KB) {
-      gemv_lane<KB>(job, job.lut_off_b, block, tid, lds, table_bytes);
+      gemv_lane<KB, NB>(job, job.lut_off_b, block, tid, lds, table_bytes);
       return;
     }
   }
-  gemv_lane<KA>(job, job.lut_off_a, block, tid, lds, table_bytes);
+  gemv_lane<KA, NB>(job, job.lut_off_a, block, tid, lds, table_bytes);
 }
 
-// jobs == nullptr: the job passed by value, for njobs right-hand sides, one after the other (sample s reads
-// x + s * in and writes y + s * out; workgroups [s * nblocks, (s + 1) * nblocks) serve it); else block b belongs
-// to the last job of the table whose block_start <= b
-template <int KA, int KB>
+// jobs == nullptr: the job passed by value, for njobs right-hand sides in groups of NB that share one pass over
+// the planes (group g reads x + g * NB * in and writes y + g * NB * out; workgroups [g * nblocks, (g + 1) *
+// nblocks) serve it); else (NB = 1) block b belongs to the last job of the table whose block_start <= b
+template <int KA, int KB, int NB>
 __global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
   // the tables sit at LDS address 0, which the lookup addresses assume
-  __shared__ __attribute__((aligned(16))) char lds[lane_lds_bytes<KA, KB>()];
+  __shared__ __attribute__((aligned(16))) char lds[lane_lds_bytes<KA, KB, NB>()];
   if (jobs == nullptr) {
-    const int sample = blockIdx.x / one.nblocks;
-    one.x += (size_t)sample * one.ncw * 32;
-    one.y += (size_t)sample * one.out;
-    gemv_lane_block<KA, KB>(one, blockIdx.x - sample * one.nblocks, threadIdx.x, lds);
+    const int group = blockIdx.x / one.nblocks;
+    one.x += (size_t)group * NB * one.ncw * 32;
+    one.y += (size_t)group * NB * one.out;
+    one.nsamples = min(NB, njobs - group * NB);
+    gemv_lane_block<KA, KB, NB>(one, blockIdx.x - group * one.nblocks, threadIdx.x, lds);
     return;
   }
-  const int b = blockIdx.x;
-  int lo = 0, hi = njobs - 1;
-  while (lo < hi) {
-    int mid = (lo + hi + 1) >> 1;
-    if (jobs[mid].block_start <= b) lo = mid; else hi = mid - 1;
+  if constexpr (NB == 1) {
+    const int b = blockIdx.x;
+    int lo = 0, hi = njobs - 1;
+    while (lo < hi) {
+      int mid = (lo + hi + 1) >> 1;
+      if (jobs[mid].block_start <= b) lo = mid; else hi = mid - 1;
+    }
+    GemvJob job = jobs[lo];
+    gemv_lane_block<KA, KB, 1>(job, b - job.block_start, threadIdx.x, lds);
   }
-  GemvJob job = jobs[lo];
-  gemv_lane_block<KA, KB>(job, b - job.block_start, threadIdx.x, lds);
 }
 
 }  // namespace dpllm
