@@ -61,6 +61,8 @@ struct Phase {
   int part_first, part_count;   // slice of the device selector part table
   std::vector<GemvLaunch> gemv;
 };
+constexpr int kLanePoolRows = 8192;
+
 struct StepPlan {
   bool valid = false;
   uint64_t version = 0;
@@ -88,6 +90,10 @@ struct dpllm_model {
   double* d_sel_ws = nullptr;       // one slot per selector part of the plan
   double* d_sel_ws_one = nullptr;   // kSelMaxParts slots for dpllm_estimate
   GemvJob* d_gemv_jobs = nullptr;
+  // column-split launches of the row-per-lane kernel: partial sums (kLanePoolRows x 64 fp32) and arrival counters
+  // (kLanePoolRows, zero whenever no launch is running); one launch at a time uses them
+  float* d_lane_ws = nullptr;
+  uint32_t* d_lane_cnt = nullptr;
   int device = 0;
 };
 
@@ -208,6 +214,9 @@ GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, c
   j.nblocks = lin.L.nrq;
   j.block_start = 0;
   j.nsamples = 1;
+  j.nsplit = 1;
+  j.ws = nullptr;
+  j.cnt = nullptr;
   return j;
 }
 
@@ -227,6 +236,19 @@ int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks) {
   long r = std::min<long>(8, std::max<long>(1, 393216 / std::max<long>(1, bytes_per_block)));
   while (r > 1 && total_blocks / r < 1024) --r;
   return (int)r;
+}
+
+// Row-per-lane arrangement, launches with fewer workgroups than compute units (a workgroup is tied to 64 rows):
+// the workgroups that share a block of rows.  Measured on 4096 .. 28672 rows x 4096 .. 14336 columns: splitting
+// pays only below about one workgroup per compute unit (64 blocks of rows: 23 -> 12 us at 14336 columns) and costs
+// above it (172 blocks: 9 -> 12 us), since every split builds the tables again and runs fewer tiles per wavefront.
+// workgroups = those of the whole launch before splitting; rows = blocks of rows x samples per pass x groups of
+// the job; pool = what is left of the partial-sum pool.
+int pick_lane_split(const LinearLayout& L, long workgroups, long rows, long pool) {
+  long s = std::min<long>(8, 320 / std::max<long>(1, workgroups));
+  s = std::min<long>(s, L.ncc / kLaneWaves);   // at least one tile per wavefront
+  while (s > 1 && rows * s > pool) --s;
+  return (int)std::max<long>(1, s);
 }
 
 template <int B>
@@ -268,6 +290,13 @@ int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t
   GemvJob j = make_gemv_job(lin, ka, kb, k_dev, x, y);
   const int rpb = lin.L.mode == kLayoutRowLane ? pick_blocks_per_group(lin.L, kb, lin.L.nrq) : pick_rq_per_block(lin.L.nrq);
   j.nblocks = (lin.L.nrq + rpb - 1) / rpb;
+  if (lin.L.mode == kLayoutRowLane) {
+    const long groups = B > 1 ? (B + 1) / 2 : 1, per_pass = B > 1 ? 2 : 1;
+    j.nsplit = pick_lane_split(lin.L, j.nblocks * groups, (long)lin.L.nrq * per_pass * groups, kLanePoolRows);
+    j.nblocks *= j.nsplit;
+    j.ws = m->d_lane_ws;
+    j.cnt = m->d_lane_cnt;
+  }
   launch_fast(lin.L.mode, ka, kb, nullptr, B, j, j.nblocks * B, st);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
@@ -349,6 +378,15 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       for (int j = id; j < end; ++j)
         if (cls_of(j) == c) total_rq += m->linears[j].L.nrq;
       const int rpb_quad = pick_rq_per_block(total_rq);
+      long lane_groups = 0;   // workgroups of the launch in the row-per-lane arrangement, before any split
+      if (c.mode == kLayoutRowLane)
+        for (int j = id; j < end; ++j)
+          if (cls_of(j) == c) {
+            const LinearLayout& L = m->linears[j].L;
+            const int rpb = pick_blocks_per_group(L, c.kb, total_rq);
+            lane_groups += (L.nrq + rpb - 1) / rpb;
+          }
+      long pool_used = 0;
       int blocks = 0;
       for (int j = id; j < end; ++j) {
         if (!(cls_of(j) == c)) continue;
@@ -357,6 +395,13 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
         GemvJob gj = make_gemv_job(lin, s.l, s.h, s.l == s.h ? nullptr : k_dev + j, xs[j], ys[j]);
         const int rpb = c.mode == kLayoutRowLane ? pick_blocks_per_group(lin.L, s.h, total_rq) : rpb_quad;
         gj.nblocks = (lin.L.nrq + rpb - 1) / rpb;
+        if (c.mode == kLayoutRowLane) {
+          gj.nsplit = pick_lane_split(lin.L, lane_groups, lin.L.nrq, kLanePoolRows - pool_used);
+          gj.nblocks *= gj.nsplit;
+          gj.ws = m->d_lane_ws + pool_used * 64;
+          gj.cnt = m->d_lane_cnt + pool_used;
+          pool_used += (long)lin.L.nrq * gj.nsplit;
+        }
         gj.block_start = blocks;
         blocks += gj.nblocks;
         P.gemv_jobs.push_back(gj);
@@ -396,6 +441,8 @@ void free_device(dpllm_model* m) {
   if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
   if (m->d_sel_ws_one) (void)hipFree(m->d_sel_ws_one);
   if (m->d_gemv_jobs) (void)hipFree(m->d_gemv_jobs);
+  if (m->d_lane_ws) (void)hipFree(m->d_lane_ws);
+  if (m->d_lane_cnt) (void)hipFree(m->d_lane_cnt);
 }
 
 }  // namespace
@@ -409,6 +456,15 @@ int dpllm_model_create(dpllm_model** out, int n_linears) {
   if (!m) return DPLLM_EINVAL;
   m->linears.resize(n_linears);
   if (hipGetDevice(&m->device) != hipSuccess) {
+    (void)hipGetLastError();
+    free_device(m);
+    delete m;
+    return DPLLM_EHIP;
+  }
+  if (hipMalloc((void**)&m->d_lane_ws, sizeof(float) * 64 * kLanePoolRows) != hipSuccess ||
+      hipMalloc((void**)&m->d_lane_cnt, sizeof(uint32_t) * kLanePoolRows) != hipSuccess ||
+      hipMemset(m->d_lane_cnt, 0, sizeof(uint32_t) * kLanePoolRows) != hipSuccess ||
+      hipDeviceSynchronize() != hipSuccess) {
     (void)hipGetLastError();
     free_device(m);
     delete m;

@@ -47,6 +47,12 @@ struct GemvJob {
   int32_t block_start;        // index of this job's first workgroup inside a multi-job grid
   int32_t nsamples;           // right-hand sides served together (1..NB): sample s reads x + s * in, writes y + s * out
   int32_t ncc;                // row-per-lane layout: 128-column tiles per row (there nrq counts blocks of 64 rows)
+  // row-per-lane layout, column split: nsplit workgroups share every block of rows, each taking 1 / nsplit of its
+  // column tiles (nblocks counts all of them).  Their fp32 partial sums meet in ws ([row block][sample][split]
+  // [64 rows]); cnt ([row block][sample], zero between launches) tells the last one to arrive, which adds them up.
+  int32_t nsplit;
+  float* ws;
+  uint32_t* cnt;
 };
 
 __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }

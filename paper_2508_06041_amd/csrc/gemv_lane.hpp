@@ -368,19 +368,24 @@ __device__ __forceinline__ void lane_group_barrier() {
 template <int K, int NB>
 constexpr int kLaneDepth = (K <= 4 && NB == 1) ? 3 : 2;
 
-// One workgroup: row blocks block, block + nblocks, ... of a job; wavefront w takes the column tiles
-// [w ncc / 8, (w + 1) ncc / 8) of every row block.  Tile loads run kLaneDepth - 1 tiles ahead, also across row
-// blocks; past the end of the run the ring is refilled with dummy loads (see lane_load_tile).
+// One workgroup: row blocks block, block + step, ... of a job (step = nblocks / nsplit); it is number `split` of
+// the nsplit workgroups that share these row blocks, and its wavefront w takes slice v = 8 split + w of the
+// 8 nsplit slices of the column tiles, [v ncc / (8 nsplit), (v + 1) ncc / (8 nsplit)), in every row block.  Tile
+// loads run kLaneDepth - 1 tiles ahead, also across row blocks; past the end of the run the ring is refilled with
+// dummy loads (see lane_load_tile).
 template <int K, int NB>
-__device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int tid, char* lds, int table_bytes) {
+__device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int split, int tid, char* lds,
+                                          int table_bytes) {
   constexpr int D = kLaneDepth<K, NB>;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const uint32_t lanecol = (uint32_t)lane * 4;  // the lane's column of the interleaved tables
   float* red = reinterpret_cast<float*>(lds + table_bytes);
   char* slot = lds + table_bytes + NB * kLaneRedBytes + wave * lane_x_bytes<NB>();
-  const int c0 = wave * job.ncc / kLaneWaves, c1 = (wave + 1) * job.ncc / kLaneWaves;
+  const int nsplit = job.nsplit;
+  const int slice = split * kLaneWaves + wave, nslices = nsplit * kLaneWaves;
+  const int c0 = slice * job.ncc / nslices, c1 = (slice + 1) * job.ncc / nslices;
   const int nrb = job.nrq;                     // row blocks of the job
-  const int step = job.nblocks;
+  const int step = job.nblocks / nsplit;
   const DPLLM_GLOBAL uint16_t* lut_base = as_global(reinterpret_cast<const uint16_t*>(job.arena + lut_off));
   const bool idle = c0 >= c1;                  // fewer tiles than wavefronts: this one only helps with the tables
   // the table rows of the next row block travel one block ahead, except at k >= 7, where their 8 - 16 registers
@@ -429,8 +434,30 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       float s = 0.f;
 #pragma unroll
       for (int w = 0; w < kLaneWaves; ++w) s += red[(wave * kLaneWaves + w) * 64 + lane];
+      bool last = true;
+      if (nsplit > 1) {
+        // every workgroup of the row block leaves its sums, then takes a ticket; the holder of the last ticket
+        // finds all of them, adds them in the order of the splits and leaves the counter at zero again.  The sums
+        // travel as device-scope atomic stores and loads, which pass through the per-die caches by themselves:
+        // waiting for the store to be acknowledged before taking the ticket orders them, and no cache has to be
+        // written back or invalidated as a whole (what a device-scope fence would do, at several times the cost
+        // of the launch)
+        DPLLM_GLOBAL float* part = as_global(job.ws) + (size_t)(rb * NB + wave) * nsplit * 64 + lane;
+        DPLLM_GLOBAL uint32_t* ticket = as_global(job.cnt) + rb * NB + wave;
+        __hip_atomic_store(part + split * 64, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        uint32_t old = 0;
+        if (lane == 0) old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = __builtin_amdgcn_readfirstlane(old) == (uint32_t)(nsplit - 1);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        if (last) {
+          s = 0.f;
+          for (int i = 0; i < nsplit; ++i) s += __hip_atomic_load(part + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (lane == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
       const int o = rb * 64 + lane;
-      if (o < job.out) as_global(job.y)[(size_t)wave * job.out + o] = __builtin_bit_cast(uint16_t, (_Float16)s);
+      if (last && o < job.out) as_global(job.y)[(size_t)wave * job.out + o] = __builtin_bit_cast(uint16_t, (_Float16)s);
     }
   };
   open_block();
@@ -466,15 +493,17 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
 
 template <int KA, int KB, int NB>
 __device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, int tid, char* lds) {
+  const int split = block % job.nsplit;
+  block /= job.nsplit;
   if (block >= job.nrq) return;
   constexpr int table_bytes = lane_table_bytes<KA, KB>();
   if constexpr (KA != KB) {
     if (job.k_dev != nullptr && __builtin_amdgcn_readfirstlane(*as_global(job.k_dev)) == KB) {
-      gemv_lane<KB, NB>(job, job.lut_off_b, block, tid, lds, table_bytes);
+      gemv_lane<KB, NB>(job, job.lut_off_b, block, split, tid, lds, table_bytes);
       return;
     }
   }
-  gemv_lane<KA, NB>(job, job.lut_off_a, block, tid, lds, table_bytes);
+  gemv_lane<KA, NB>(job, job.lut_off_a, block, split, tid, lds, table_bytes);
 }
 
 // jobs == nullptr: the job passed by value, for njobs right-hand sides in groups of NB that share one pass over
@@ -489,6 +518,8 @@ __global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* 
     one.x += (size_t)group * NB * one.ncw * 32;
     one.y += (size_t)group * NB * one.out;
     one.nsamples = min(NB, njobs - group * NB);
+    one.ws += (size_t)group * one.nrq * NB * one.nsplit * 64;
+    one.cnt += (size_t)group * one.nrq * NB;
     gemv_lane_block<KA, KB, NB>(one, blockIdx.x - group * one.nblocks, threadIdx.x, lds);
     return;
   }

@@ -36,6 +36,10 @@ def rel_l2(got, ref):
     return np.linalg.norm(np.asarray(got, dtype=np.float64) - ref) / max(np.linalg.norm(ref), 1e-300)
 
 
+def same_up_to_sum_order(a, b):
+    return torch.equal(a, b) or rel_l2(a.float().cpu().numpy(), b.double().cpu().numpy()) <= 2e-4
+
+
 def run_step_checks(dp, model, meta, l, h, steps, check_all_single=True):
     import bench  # noqa: F401  (build_model lives there)
     shapes = meta["shapes"]
@@ -67,10 +71,12 @@ def run_step_checks(dp, model, meta, l, h, steps, check_all_single=True):
             k = int(ks[i])
             y_ref = oracle.gemv(ref["planes"], k, ref["luts"][k], x_np[shapes[i][1]])
             assert rel_l2(ys[i].float().cpu().numpy(), y_ref) <= REL_L2, (i, t, k)
-        if check_all_single:                           # multi-job launch == single-linear launch, bitwise
+        if check_all_single:
+            # multi-job launch == single-linear launch: bitwise, unless the small launch split the columns of a
+            # row over several workgroups (row-per-lane arrangement), which changes the order of the fp32 sums
             for i in range(n):
                 y1 = model.dpllm_gemv(i, int(ks[i]), xs[i])
-                assert torch.equal(y1, ys[i]), (i, t)
+                assert same_up_to_sum_order(y1, ys[i]), (i, t)
     return seen
 
 
@@ -100,7 +106,7 @@ def test_decode_step_llama7b_full(dp):
             y_ref = oracle.gemv(ref["planes"], k, ref["luts"][k], synth.lut_np(xs[i]))
             assert rel_l2(ys[i].float().cpu().numpy(), y_ref) <= REL_L2, (i, k)
         for i in range(0, n, 5):
-            assert torch.equal(model.dpllm_gemv(i, k, xs[i]), ys[i]), (i, k)
+            assert same_up_to_sum_order(model.dpllm_gemv(i, k, xs[i]), ys[i]), (i, k)
     model.close()
 
 

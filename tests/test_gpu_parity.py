@@ -471,3 +471,45 @@ def test_gemv_many_rows_several_row_quads_per_wavefront(dp, out, in_):
         assert rel_l2(got1, ref[0]) <= REL_L2, k
         assert rel_l2(got2[0], ref[0]) <= REL_L2 and rel_l2(got2[1], ref[1]) <= REL_L2, k
     model.close()
+
+
+@pytest.mark.parametrize("out,in_", [(200, 3072), (64, 8192 + 32), (130, 2080), (1, 16384)])
+def test_gemv_few_rows_long_columns(dp, out, in_):
+    """Launches with far fewer blocks of rows than compute units: in the row-per-lane arrangement several
+    workgroups share a block of rows and the last one to finish adds up their partial sums.  Single calls with
+    one to three samples and a decode step; every call twice, which must give the same bits (the arrival counters
+    are back at zero, the order of the additions is fixed)."""
+    lin = synth.make_linear(out, in_, 8, 3, seed=out + in_)
+    other = synth.make_linear(96, in_, 8, 3, seed=out + in_ + 1)
+    model = load(dp, [lin, other])
+    X = synth.make_x(in_, 3, seed=31)
+    planes = synth.planes_np(lin["planes"])
+    for k in range(3, 9):
+        ref = oracle.gemv(planes, k, synth.lut_np(lin["luts"][k]), synth.lut_np(X))
+        for B in (1, 2, 3):
+            xb = (X[:B] if B > 1 else X[0]).cuda()
+            got = model.dpllm_gemv(0, k, xb)
+            again = model.dpllm_gemv(0, k, xb)
+            assert torch.equal(got, again), (k, B)
+            got = got.float().cpu().numpy().reshape(B, out)
+            for b in range(B):
+                assert rel_l2(got[b], ref[b]) <= REL_L2, (k, B, b)
+    # both linears in one launch of the decode step
+    xs = [X[0].cuda(), X[1].cuda()]
+    ys = [torch.empty(out, dtype=torch.float16, device="cuda"), torch.empty(96, dtype=torch.float16, device="cuda")]
+    k_dev = torch.zeros(2, dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(2, dtype=torch.float32, device="cuda")
+    for k in (3, 6):
+        for i in range(2):
+            model.dpllm_set_selector(i, k, k, dp.DPLLM_SEL_NONE)
+        first = None
+        for _ in range(2):
+            model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+            torch.cuda.synchronize()
+            if first is None:
+                first = [y.clone() for y in ys]
+        assert all(torch.equal(a, b) for a, b in zip(first, ys))
+        for i, l in enumerate((lin, other)):
+            ref = oracle.gemv(synth.planes_np(l["planes"]), k, synth.lut_np(l["luts"][k]), synth.lut_np(X[i]))
+            assert rel_l2(ys[i].float().cpu().numpy(), ref) <= REL_L2, (k, i)
+    model.close()
