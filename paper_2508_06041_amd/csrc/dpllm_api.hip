@@ -62,6 +62,7 @@ struct Phase {
   std::vector<GemvLaunch> gemv;
 };
 constexpr int kLanePoolRows = 8192;
+constexpr size_t kSelOneSlots = (size_t)kSelMaxChunks * kSelMaxRank;
 
 struct StepPlan {
   bool valid = false;
@@ -87,8 +88,10 @@ struct dpllm_model {
   SelJob* d_sel_jobs = nullptr;
   SelPart* d_sel_parts = nullptr;
   size_t sel_parts_cap = 0;
-  double* d_sel_ws = nullptr;       // one slot per selector part of the plan
-  double* d_sel_ws_one = nullptr;   // kSelMaxParts slots for dpllm_estimate
+  double* d_sel_ws = nullptr;       // the workspace slots of every selector job of the plan
+  size_t sel_ws_cap = 0;
+  double* d_sel_ws_one = nullptr;   // kSelMaxChunks x kSelMaxRank slots for dpllm_estimate, then its arrival counter
+  uint32_t* d_sel_tickets = nullptr;  // one arrival counter per linear of the plan, zero between launches
   GemvJob* d_gemv_jobs = nullptr;
   // column-split launches of the row-per-lane kernel: partial sums (kLanePoolRows x 64 fp32) and arrival counters
   // (kLanePoolRows, zero whenever no launch is running); one launch at a time uses them
@@ -136,7 +139,9 @@ Linear* get_linear(dpllm_model* m, int id, int* rc) {
 }
 
 // ---- selector ---------------------------------------------------------------------------------------------
-SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* e_dev, int32_t* k_dev) {
+// launch_rowgroups: groups of 16 rows of G over all jobs of the launch.  A launch with fewer of them than
+// would fill the chip cuts the columns into chunks (multiples of 512 columns) as well.
+SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* e_dev, int32_t* k_dev, long launch_rowgroups) {
   SelJob j;
   j.G = s.G;
   j.x = (const uint16_t*)x;
@@ -145,8 +150,18 @@ SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* 
   j.T = s.T; j.alpha = s.alpha; j.beta = s.beta;
   j.in = lin.L.in; j.r = s.r;
   j.l = s.l; j.h = s.h; j.kind = s.kind;
-  j.nparts = sel_parts_of(s.kind, s.r);
+  j.nchunks = 1;
+  j.chunk_cols = lin.L.in;
+  if (s.kind == 1) {
+    const long want = std::min<long>(kSelMaxChunks, 512 / std::max<long>(1, launch_rowgroups));
+    if (want > 1) {
+      j.chunk_cols = (int)((lin.L.in + want - 1) / want + kSelChunkStep - 1) / kSelChunkStep * kSelChunkStep;   // <= want chunks
+      j.nchunks = (lin.L.in + j.chunk_cols - 1) / j.chunk_cols;
+    }
+  }
+  j.nparts = sel_rowgroups_of(s.kind, s.r) * j.nchunks;
   j.ws = nullptr;
+  j.ticket = nullptr;
   return j;
 }
 
@@ -323,6 +338,8 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   if (!m->d_sel_jobs) {
     HIP_TRY(m, hipMalloc((void**)&m->d_sel_jobs, sizeof(SelJob) * n));
     HIP_TRY(m, hipMalloc((void**)&m->d_gemv_jobs, sizeof(GemvJob) * n));
+    HIP_TRY(m, hipMalloc((void**)&m->d_sel_tickets, sizeof(uint32_t) * n));
+    HIP_TRY(m, hipMemset(m->d_sel_tickets, 0, sizeof(uint32_t) * n));
   }
   std::vector<SelJob> sel_jobs;
   std::vector<SelPart> sel_parts;
@@ -348,13 +365,18 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     ph.sel_first = (int)sel_jobs.size();
     ph.sel_count = end - id;
     ph.part_first = (int)sel_parts.size();
+    long launch_rowgroups = 0;
+    for (int j = id; j < end; ++j) {
+      const Selector& s = m->linears[j].sel[m->linears[j].active];
+      launch_rowgroups += sel_rowgroups_of(s.kind, s.r);
+    }
     for (int j = id; j < end; ++j) {
       const Linear& lin = m->linears[j];
       const Selector& s = lin.sel[lin.active];
-      SelJob sj = make_sel_job(lin, s, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j);
+      SelJob sj = make_sel_job(lin, s, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j, launch_rowgroups);
       for (int part = 0; part < sj.nparts; ++part) sel_parts.push_back(SelPart{j - id, part});
       ws_offset.push_back(ws_slots);
-      ws_slots += (size_t)sj.nparts;
+      ws_slots += (size_t)sel_slots_of(s.kind, s.r, sj.nchunks);
       sel_jobs.push_back(sj);
     }
     ph.part_count = (int)sel_parts.size() - ph.part_first;
@@ -418,13 +440,20 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   HIP_TRY(m, hipStreamSynchronize(st));
   if (sel_parts.size() > m->sel_parts_cap) {
     if (m->d_sel_parts) (void)hipFree(m->d_sel_parts);
-    if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
-    m->d_sel_parts = nullptr; m->d_sel_ws = nullptr; m->sel_parts_cap = 0;
+    m->d_sel_parts = nullptr; m->sel_parts_cap = 0;
     HIP_TRY(m, hipMalloc((void**)&m->d_sel_parts, sizeof(SelPart) * sel_parts.size()));
-    HIP_TRY(m, hipMalloc((void**)&m->d_sel_ws, sizeof(double) * sel_parts.size()));
     m->sel_parts_cap = sel_parts.size();
   }
-  for (size_t i = 0; i < sel_jobs.size(); ++i) sel_jobs[i].ws = m->d_sel_ws ? m->d_sel_ws + ws_offset[i] : nullptr;
+  if (ws_slots > m->sel_ws_cap) {
+    if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
+    m->d_sel_ws = nullptr; m->sel_ws_cap = 0;
+    HIP_TRY(m, hipMalloc((void**)&m->d_sel_ws, sizeof(double) * ws_slots));
+    m->sel_ws_cap = ws_slots;
+  }
+  for (size_t i = 0; i < sel_jobs.size(); ++i) {
+    sel_jobs[i].ws = m->d_sel_ws + ws_offset[i];
+    sel_jobs[i].ticket = m->d_sel_tickets + i;
+  }
   if (!sel_parts.empty())
     HIP_TRY(m, hipMemcpy(m->d_sel_parts, sel_parts.data(), sizeof(SelPart) * sel_parts.size(), hipMemcpyHostToDevice));
   HIP_TRY(m, hipMemcpy(m->d_sel_jobs, sel_jobs.data(), sizeof(SelJob) * sel_jobs.size(), hipMemcpyHostToDevice));
@@ -440,6 +469,7 @@ void free_device(dpllm_model* m) {
   if (m->d_sel_parts) (void)hipFree(m->d_sel_parts);
   if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
   if (m->d_sel_ws_one) (void)hipFree(m->d_sel_ws_one);
+  if (m->d_sel_tickets) (void)hipFree(m->d_sel_tickets);
   if (m->d_gemv_jobs) (void)hipFree(m->d_gemv_jobs);
   if (m->d_lane_ws) (void)hipFree(m->d_lane_ws);
   if (m->d_lane_cnt) (void)hipFree(m->d_lane_cnt);
@@ -633,14 +663,17 @@ int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, floa
   if ((uintptr_t)x_dev % 16) return fail(m, DPLLM_EINVAL, "x not 16-byte aligned");
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
-  SelJob j = make_sel_job(*lin, lin->sel[slot], x_dev, e_dev, k_dev);
-  if (!m->d_sel_ws_one) HIP_TRY(m, hipMalloc((void**)&m->d_sel_ws_one, sizeof(double) * kSelMaxParts));
+  const Selector& sel = lin->sel[slot];
+  SelJob j = make_sel_job(*lin, sel, x_dev, e_dev, k_dev, sel_rowgroups_of(sel.kind, sel.r));
+  if (!m->d_sel_ws_one) {
+    HIP_TRY(m, hipMalloc((void**)&m->d_sel_ws_one, sizeof(double) * (kSelOneSlots + 1)));
+    HIP_TRY(m, hipMemset(m->d_sel_ws_one + kSelOneSlots, 0, sizeof(double)));
+    HIP_TRY(m, hipDeviceSynchronize());
+  }
   j.ws = m->d_sel_ws_one;
-  if (j.nparts > 0)
-    hipLaunchKernelGGL(selector_part_kernel, dim3(j.nparts), dim3(kSelPartThreads), 0, (hipStream_t)stream,
-                       (const SelJob*)nullptr, (const SelPart*)nullptr, j);
-  hipLaunchKernelGGL(selector_decide_kernel, dim3(1), dim3(kSelDecideThreads), 0, (hipStream_t)stream,
-                     (const SelJob*)nullptr, 1, j);
+  j.ticket = reinterpret_cast<uint32_t*>(m->d_sel_ws_one + kSelOneSlots);
+  hipLaunchKernelGGL(selector_part_kernel, dim3(j.nparts), dim3(kSelPartThreads), 0, (hipStream_t)stream,
+                     (const SelJob*)nullptr, (const SelPart*)nullptr, j);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -689,11 +722,8 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
   for (const Phase& ph : P.phases) {
     if (parts & DPLLM_STEP_SELECT) {
       const SelJob* jobs = m->d_sel_jobs + ph.sel_first;
-      if (ph.part_count > 0)
-        hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
-                           (const SelPart*)(m->d_sel_parts + ph.part_first), none);
-      hipLaunchKernelGGL(selector_decide_kernel, dim3((ph.sel_count + kSelDecideThreads - 1) / kSelDecideThreads),
-                         dim3(kSelDecideThreads), 0, st, jobs, ph.sel_count, none);
+      hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
+                         (const SelPart*)(m->d_sel_parts + ph.part_first), none);
     }
     if (!(parts & DPLLM_STEP_GEMV)) continue;
     for (const GemvLaunch& gl : ph.gemv) {

@@ -1,13 +1,17 @@
 // Precision selector kernels (paper Sec. 3: the layer takes h when the relative error exceeds its threshold
 // T, else l; Sec. 5.1: the error is estimated as ||G x|| with G = A (W_h - W_l) precomputed, or as
-// alpha ||x|| + beta).  One pair of launches serves a list of selector jobs; the bitwidth lands in device
-// memory, where the GEMV kernels read it.
+// alpha ||x|| + beta).  One launch serves a list of selector jobs; the bitwidth lands in device memory, where
+// the GEMV kernels read it.
 //
 // A job reads 0.5 - 3.5 MB of G.  It is cut into parts of 16 rows of G (one workgroup of four wavefronts,
-// four rows per wavefront sharing the activation loads); a part writes the fp64 sum of its g_j^2 to a
-// workspace slot of its own.  A second, tiny kernel adds the slots of every job in index order, takes the
-// square root and the decision.  No atomics and no fences: the order of all additions is fixed, and the
-// parts of long jobs spread over the whole chip instead of occupying one compute unit each.
+// four rows per wavefront sharing the activation loads) by a chunk of columns: the whole row when the launch
+// has enough parts to fill the chip, down to 512 columns when it serves a few linears only (a part that
+// streams a whole row alone takes 10 - 30 us).  A part leaves the fp64 partial dot products of its rows in
+// workspace slots of its own and takes a ticket from the job's counter; the part that draws the last ticket
+// adds the partial products of every row in chunk order, squares, adds the rows in index order, takes the
+// square root and the decision, and leaves the counter at zero for the next launch.  The order of all
+// additions is fixed whichever part comes last.  (A separate kernel for this last step would cost a dependent
+// launch per group of linears that run together.)
 //
 // The estimate and the compare are taken in fp64: fp16 x fp16 products are exact in fp32, their sum runs in
 // fp64 in a fixed order, so a decision is reproducible and differs from an ideal-arithmetic decision only
@@ -26,26 +30,32 @@ constexpr int kSelRowsPerWave = 4;   // rows of G a wavefront carries at once (t
 constexpr int kSelDepth = 2;         // column tiles in registers: one being accumulated, one in flight
 constexpr int kSelPartRows = kSelPartWaves * kSelRowsPerWave;
 constexpr int kSelMaxRank = 1024;
-constexpr int kSelMaxParts = kSelMaxRank / kSelPartRows;
-constexpr int kSelDecideThreads = 256;
+constexpr int kSelMaxChunks = 32;    // column chunks of a job
+constexpr int kSelChunkStep = 512;   // columns a wavefront covers per tile: chunks are multiples of it
 
 struct SelJob {
   const uint16_t* G;   // fp16 [r][in] (projection kind)
   const uint16_t* x;   // fp16 [in]
   float* e_out;
   int32_t* k_out;
-  double* ws;          // nparts workspace slots of this job
+  double* ws;          // projection: [nchunks][16 rowgroups] partial dot products; else one slot
+  uint32_t* ticket;    // arrival counter of this job, zero between launches
   float T, alpha, beta;
   int32_t in, r, l, h, kind;  // kind: 0 none, 1 projection, 2 linear regression
-  int32_t nparts;             // projection: ceil(r / 16); linear regression: 1; none: 0
+  int32_t nparts;             // projection: rowgroups * nchunks; linear regression: 1; none: 1 (only the decision)
+  int32_t nchunks, chunk_cols;  // projection: part p covers rows [16 (p / nchunks), + 16), columns [chunk_cols (p % nchunks), + chunk_cols)
 };
 struct SelPart {
   int32_t job;    // index into the job table of the launch
   int32_t part;   // part number inside the job: rows [16 part, 16 part + 16)
 };
 
-__host__ __device__ inline int sel_parts_of(int kind, int r) {
-  return kind == 1 ? (r + kSelPartRows - 1) / kSelPartRows : (kind == 2 ? 1 : 0);
+__host__ __device__ inline int sel_rowgroups_of(int kind, int r) {
+  return kind == 1 ? (r + kSelPartRows - 1) / kSelPartRows : 1;
+}
+// workspace slots (doubles) of a job
+__host__ __device__ inline int sel_slots_of(int kind, int r, int nchunks) {
+  return kind == 1 ? sel_rowgroups_of(kind, r) * kSelPartRows * nchunks : 1;
 }
 
 __device__ __forceinline__ double wave_sum_f64(double v) {
@@ -88,9 +98,24 @@ __device__ __forceinline__ void sel_accumulate(const SelTile& t, bool valid, dou
   }
 }
 
+// the estimate from the sum of squares, and the decision
+__device__ __forceinline__ void selector_decide(const SelJob& job, double tot) {
+  double e = 0.0;
+  if (job.kind == 1) e = sqrt(tot);
+  else if (job.kind == 2) e = (double)job.alpha * sqrt(tot) + (double)job.beta;
+  *job.e_out = (float)e;
+  // strictly exceeding T selects h; +inf pins l, -inf pins h; no estimator: always l
+  *job.k_out = (job.kind != 0 && e > (double)job.T) ? job.h : job.l;
+}
+
 __device__ __forceinline__ void selector_part(const SelJob& job, int part, int tid) {
-  __shared__ double red[kSelPartRows];
+  __shared__ double sq[kSelMaxRank];
+  __shared__ uint32_t is_last;
   const int wave = tid >> 6, lane = tid & 63;
+  if (job.kind == 0) {   // no estimator: only the decision
+    if (tid == 0) selector_decide(job, 0.0);
+    return;
+  }
   if (job.kind == 2) {   // sum of x^2, one part
     double acc = 0.0;
     for (int c = tid * 8; c < job.in; c += kSelPartThreads * 8) {
@@ -103,56 +128,80 @@ __device__ __forceinline__ void selector_part(const SelJob& job, int part, int t
       }
     }
     acc = wave_sum_f64(acc);
-    if (lane == 0) red[wave] = acc;
+    if (lane == 0) sq[wave] = acc;
     __syncthreads();
     if (tid == 0) {
       double tot = 0.0;
-      for (int w = 0; w < kSelPartWaves; ++w) tot += red[w];
-      job.ws[0] = tot;
+      for (int w = 0; w < kSelPartWaves; ++w) tot += sq[w];
+      selector_decide(job, tot);
     }
     return;
   }
-  // projection: wavefront w owns rows 16 part + 4 w .. + 3 (clamped to r - 1; surplus rows are dropped)
-  const int row0 = part * kSelPartRows + wave * kSelRowsPerWave;
+  // projection: wavefront w owns rows 16 rg + 4 w .. + 3 (clamped to r - 1; surplus rows are dropped), columns
+  // [cb, ce) of them
+  const int rg = part / job.nchunks, ch = part - rg * job.nchunks;
+  const int cb = ch * job.chunk_cols, ce = min(job.in, cb + job.chunk_cols);
+  const int row0 = rg * kSelPartRows + wave * kSelRowsPerWave;
   const uint16_t* rows[kSelRowsPerWave];
 #pragma unroll
   for (int i = 0; i < kSelRowsPerWave; ++i) rows[i] = job.G + (size_t)min(row0 + i, job.r - 1) * job.in;
   double acc[kSelRowsPerWave];
 #pragma unroll
   for (int i = 0; i < kSelRowsPerWave; ++i) acc[i] = 0.0;
-  const int last = job.in - 8;          // in % 32 == 0, so every 8-column group is whole
-  const int nit = (job.in + 511) / 512;
+  const int last = ce - 8;              // in % 32 == 0 and chunks are multiples of 512, so every 8-column group is whole
+  const int nit = (ce - cb + kSelChunkStep - 1) / kSelChunkStep;
   // Rows of G are a power-of-two number of bytes apart in the common shapes, so wavefronts that all walk the
-  // columns from 0 would hit the same few memory channels at any moment: every wavefront starts its
+  // columns from the start would hit the same few memory channels at any moment: every wavefront starts its
   // (circular) walk at a different 1 KiB column chunk.
   int it = (int)((blockIdx.x * kSelPartWaves + wave) * 5u % (unsigned)nit);   // tile being loaded
-  int ca = it * 512 + lane * 8;                                               // first column of the tile being accumulated
+  int ca = cb + it * kSelChunkStep + lane * 8;                                // first column of the tile being accumulated
   SelTile ring[kSelDepth];
 #pragma unroll
   for (int d = 0; d < kSelDepth - 1; ++d) {
-    sel_load(ring[d], rows, job.x, min(it * 512 + lane * 8, last));
+    sel_load(ring[d], rows, job.x, min(cb + it * kSelChunkStep + lane * 8, last));
     it = it + 1 == nit ? 0 : it + 1;
   }
   for (int k = 0; k < nit; k += kSelDepth) {
 #pragma unroll
     for (int d = 0; d < kSelDepth; ++d) {
       // loads past the end of the walk re-read a tile that is never accumulated (uniform, unconditional issue)
-      sel_load(ring[(d + kSelDepth - 1) % kSelDepth], rows, job.x, min(it * 512 + lane * 8, last));
+      sel_load(ring[(d + kSelDepth - 1) % kSelDepth], rows, job.x, min(cb + it * kSelChunkStep + lane * 8, last));
       it = it + 1 == nit ? 0 : it + 1;
       if (k + d < nit) sel_accumulate(ring[d], ca <= last, acc);
-      ca = ca + 512 >= nit * 512 ? ca + 512 - nit * 512 : ca + 512;
+      ca = ca + kSelChunkStep >= cb + nit * kSelChunkStep ? ca + kSelChunkStep - nit * kSelChunkStep : ca + kSelChunkStep;
     }
   }
+  // The partial products travel as device-scope atomic stores and loads (they pass the per-die caches by
+  // themselves); every store is acknowledged before the ticket is taken, so whoever draws the last ticket
+  // finds all of them.
+  const int nrows = sel_rowgroups_of(1, job.r) * kSelPartRows;
+  DPLLM_SEL_GLOBAL double* ws = (DPLLM_SEL_GLOBAL double*)job.ws;
+  DPLLM_SEL_GLOBAL uint32_t* ticket = (DPLLM_SEL_GLOBAL uint32_t*)job.ticket;
 #pragma unroll
   for (int i = 0; i < kSelRowsPerWave; ++i) {
-    double v = wave_sum_f64(acc[i]);
-    if (lane == 0) red[wave * kSelRowsPerWave + i] = (row0 + i < job.r) ? v * v : 0.0;
+    const double v = wave_sum_f64(acc[i]);
+    if (lane == 0) __hip_atomic_store(ws + (size_t)ch * nrows + row0 + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    is_last = old == (uint32_t)(job.nparts - 1);
+  }
+  __syncthreads();
+  if (!is_last) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  for (int t = tid; t < job.r; t += kSelPartThreads) {
+    double g = 0.0;
+    for (int c = 0; c < job.nchunks; ++c) g += __hip_atomic_load(ws + (size_t)c * nrows + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sq[t] = g * g;
   }
   __syncthreads();
   if (tid == 0) {
-    double sq = 0.0;
-    for (int j = 0; j < kSelPartRows; ++j) sq += red[j];
-    job.ws[part] = sq;
+    __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    double tot = 0.0;
+    for (int t = 0; t < job.r; ++t) tot += sq[t];
+    selector_decide(job, tot);
   }
 }
 
@@ -165,31 +214,6 @@ __global__ void __launch_bounds__(kSelPartThreads) selector_part_kernel(const Se
     const SelPart p = parts[blockIdx.x];
     SelJob job = jobs[p.job];
     selector_part(job, p.part, threadIdx.x);
-  }
-}
-
-__device__ __forceinline__ void selector_decide(const SelJob& job) {
-  double tot = 0.0;
-  for (int i = 0; i < job.nparts; ++i) tot += job.ws[i];
-  double e = 0.0;
-  if (job.kind == 1) e = sqrt(tot);
-  else if (job.kind == 2) e = (double)job.alpha * sqrt(tot) + (double)job.beta;
-  *job.e_out = (float)e;
-  // strictly exceeding T selects h; +inf pins l, -inf pins h; no estimator: always l
-  *job.k_out = (job.kind != 0 && e > (double)job.T) ? job.h : job.l;
-}
-
-// one thread per job; jobs == nullptr: the single job passed by value
-__global__ void __launch_bounds__(kSelDecideThreads) selector_decide_kernel(const SelJob* __restrict__ jobs, int njobs,
-                                                                             SelJob one) {
-  if (jobs == nullptr) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) selector_decide(one);
-    return;
-  }
-  const int j = blockIdx.x * kSelDecideThreads + threadIdx.x;
-  if (j < njobs) {
-    SelJob job = jobs[j];
-    selector_decide(job);
   }
 }
 
