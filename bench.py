@@ -158,7 +158,7 @@ def main():
     ms_step_eager = timed(full_step, args.steps, args.warmup)
     ms_step, launch_mode = ms_step_eager, "eager launches"
     if not args.no_graph:
-        # the same K steps recorded once in a HIP graph (per step: one input copy + three kernels) and replayed:
+        # the same K steps recorded once in a HIP graph (per step: one input copy + two kernels) and replayed:
         # what a serving loop does to shed launch gaps.  The replay's final state is checked against eager.
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
@@ -231,6 +231,28 @@ def main():
         for i in range(n):
             model.dpllm_set_active_pair(i, l, h)
 
+    # ---- the same linears with their buffers chained the way a Transformer block chains them ---------------------
+    # (q, k, v read the residual; o reads v's output; gate and up read o's output; down reads gate's output and
+    # writes the next residual): four dependent groups per block, each a selector launch and a GEMV launch of a
+    # few linears.  Reported beside the headline figure, which runs all linears of the step as one group.
+    chained = None
+    if [name for name, _, _ in shapes] == ["q", "k", "v", "o", "gate", "up", "down"]:
+        d, f = shapes[0][2], shapes[4][1]
+        res = [torch.zeros(d, dtype=torch.float16, device="cuda") for _ in range(args.blocks + 1)]
+        res[0].copy_(meta["xs_by_in"][d][0] / 1024)
+        cx, cy = [], []
+        for b in range(args.blocks):
+            q, k_, v, o = (torch.empty(d, dtype=torch.float16, device="cuda") for _ in range(4))
+            g, u = (torch.empty(f, dtype=torch.float16, device="cuda") for _ in range(2))
+            cx += [res[b], res[b], res[b], v, o, o, g]
+            cy += [q, k_, v, o, g, u, res[b + 1]]
+        cxp, cyp = model.pointers(cx), model.pointers(cy)
+        ms_chain = timed(lambda t: model.dpllm_decode_step(cxp, cyp, k_dev, e_dev), 20, 20)
+        chained = {"us_per_step": round(ms_chain * 1e3, 1), "dependent_groups": 4 * args.blocks,
+                   "launches_per_step": 8 * args.blocks}
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)   # back to the plan of the headline run
+        torch.cuda.synchronize()
+
     # ---- CPU oracle on a bounded sample: the 7 linears of block 0, one step -------------------------------
     cpu = None
     if not args.no_cpu:
@@ -275,6 +297,7 @@ def main():
         "selector": {"us_per_step": round(ms_sel * 1e3, 1), "GBps": round(sel_bytes / (ms_sel * 1e-3) / 1e9, 1),
                      "share_of_step": round(ms_sel / (ms_sel + ms_gemv), 4)},
         "per_k": per_k,
+        "chained_step": chained,
         "roofline": {"bound": "hbm", "kernel": gemv_name, "achieved": round(roof_achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(roof_achieved / HBM_PEAK_GBPS, 4),
                      "us_per_launch": round(ms_gemv * 1e3, 1), "algorithmic_bytes": int(gemv_bytes0),

@@ -54,7 +54,8 @@ struct GemvLaunch {
   int ka, kb;          // kernel instance; ka == kb == 0: the plain kernel, one launch per job
   int mode;            // arrangement of the planes of the linears in this launch
   int first, count;    // slice of the device job table
-  int blocks;
+  int blocks;          // workgroups of the launch
+  int block_first;     // slice of the device workgroup-to-job table
 };
 struct Phase {
   int sel_first, sel_count;     // slice of the device selector job table
@@ -93,6 +94,8 @@ struct dpllm_model {
   double* d_sel_ws_one = nullptr;   // kSelMaxChunks x kSelMaxRank slots for dpllm_estimate, then its arrival counter
   uint32_t* d_sel_tickets = nullptr;  // one arrival counter per linear of the plan, zero between launches
   GemvJob* d_gemv_jobs = nullptr;
+  int32_t* d_block_jobs = nullptr;   // for every workgroup of every multi-job GEMV launch of the plan: its job
+  size_t block_jobs_cap = 0;
   // column-split launches of the row-per-lane kernel: partial sums (kLanePoolRows x 64 fp32) and arrival counters
   // (kLanePoolRows, zero whenever no launch is running); one launch at a time uses them
   float* d_lane_ws = nullptr;
@@ -176,36 +179,39 @@ bool has_fast_kernel(int ka, int kb) { return ka >= 3 && kb <= 8 && (kb == ka ||
 template <int KA, int KB, int NB>
 void launch_group_t(int njobs, const GemvJob& one, hipStream_t st) {
   const int groups = (njobs + NB - 1) / NB;
-  hipLaunchKernelGGL((gemv_kernel<KA, KB, NB>), dim3(one.nblocks * groups), dim3(64), 0, st, (const GemvJob*)nullptr, njobs, one);
+  hipLaunchKernelGGL((gemv_kernel<KA, KB, NB>), dim3(one.nblocks * groups), dim3(64), 0, st, (const GemvJob*)nullptr,
+                     (const int32_t*)nullptr, njobs, one);
 }
 
 template <int KA, int KB>
-void launch_fast_t(const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
+void launch_fast_t(const GemvJob* d_jobs, const int32_t* d_block_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
   if (d_jobs == nullptr && njobs > 1) {
     // measured on 8B shapes: two samples per pass are fastest for B = 2, four per pass from B = 3 on
     if (njobs == 2) launch_group_t<KA, KB, 2>(njobs, one, st);
     else launch_group_t<KA, KB, 4>(njobs, one, st);
   } else {
-    hipLaunchKernelGGL((gemv_kernel<KA, KB, 1>), dim3(blocks), dim3(64), 0, st, d_jobs, njobs, one);
+    hipLaunchKernelGGL((gemv_kernel<KA, KB, 1>), dim3(blocks), dim3(64), 0, st, d_jobs, d_block_jobs, njobs, one);
   }
 }
 
 // row-per-lane arrangement: a batch runs in groups of two samples that share one pass over the planes
 template <int KA, int KB>
-void launch_lane_t(const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
+void launch_lane_t(const GemvJob* d_jobs, const int32_t* d_block_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
   if (d_jobs == nullptr && njobs > 1)
     hipLaunchKernelGGL((gemv_lane_kernel<KA, KB, 2>), dim3(one.nblocks * ((njobs + 1) / 2)), dim3(kLaneThreads), 0, st, d_jobs,
-                       njobs, one);
+                       d_block_jobs, njobs, one);
   else
     hipLaunchKernelGGL((gemv_lane_kernel<KA, KB, 1>), dim3(d_jobs == nullptr ? one.nblocks : blocks), dim3(kLaneThreads), 0, st,
-                       d_jobs, njobs, one);
+                       d_jobs, d_block_jobs, njobs, one);
 }
 
-void launch_fast(int mode, int ka, int kb, const GemvJob* d_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
+// d_jobs != nullptr: a table of jobs, d_block_jobs[b] = index in it of the job workgroup b works for
+void launch_fast(int mode, int ka, int kb, const GemvJob* d_jobs, const int32_t* d_block_jobs, int njobs, const GemvJob& one,
+                 int blocks, hipStream_t st) {
 #define DPLLM_CASE(A, B)                                                            \
   case (A) * 16 + (B):                                                              \
-    if (mode == kLayoutRowLane) launch_lane_t<A, B>(d_jobs, njobs, one, blocks, st); \
-    else launch_fast_t<A, B>(d_jobs, njobs, one, blocks, st);                       \
+    if (mode == kLayoutRowLane) launch_lane_t<A, B>(d_jobs, d_block_jobs, njobs, one, blocks, st); \
+    else launch_fast_t<A, B>(d_jobs, d_block_jobs, njobs, one, blocks, st);                       \
     break;
   switch (ka * 16 + kb) {
     DPLLM_CASE(3, 3) DPLLM_CASE(4, 4) DPLLM_CASE(5, 5) DPLLM_CASE(6, 6) DPLLM_CASE(7, 7) DPLLM_CASE(8, 8)
@@ -312,7 +318,7 @@ int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t
     j.ws = m->d_lane_ws;
     j.cnt = m->d_lane_cnt;
   }
-  launch_fast(lin.L.mode, ka, kb, nullptr, B, j, j.nblocks * B, st);
+  launch_fast(lin.L.mode, ka, kb, nullptr, nullptr, B, j, j.nblocks * B, st);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -343,6 +349,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   }
   std::vector<SelJob> sel_jobs;
   std::vector<SelPart> sel_parts;
+  std::vector<int32_t> block_jobs;
   std::vector<size_t> ws_offset;
   size_t ws_slots = 0;
   int id = 0;
@@ -396,6 +403,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       GemvLaunch gl;
       gl.ka = c.ka; gl.kb = c.kb; gl.mode = c.mode;
       gl.first = (int)P.gemv_jobs.size();
+      gl.block_first = (int)block_jobs.size();
       long total_rq = 0;
       for (int j = id; j < end; ++j)
         if (cls_of(j) == c) total_rq += m->linears[j].L.nrq;
@@ -426,6 +434,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
         }
         gj.block_start = blocks;
         blocks += gj.nblocks;
+        block_jobs.insert(block_jobs.end(), gj.nblocks, (int32_t)(P.gemv_jobs.size() - gl.first));
         P.gemv_jobs.push_back(gj);
         P.gemv_ids.push_back(j);
       }
@@ -444,6 +453,14 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     HIP_TRY(m, hipMalloc((void**)&m->d_sel_parts, sizeof(SelPart) * sel_parts.size()));
     m->sel_parts_cap = sel_parts.size();
   }
+  if (block_jobs.size() > m->block_jobs_cap) {
+    if (m->d_block_jobs) (void)hipFree(m->d_block_jobs);
+    m->d_block_jobs = nullptr; m->block_jobs_cap = 0;
+    HIP_TRY(m, hipMalloc((void**)&m->d_block_jobs, sizeof(int32_t) * block_jobs.size()));
+    m->block_jobs_cap = block_jobs.size();
+  }
+  if (!block_jobs.empty())
+    HIP_TRY(m, hipMemcpy(m->d_block_jobs, block_jobs.data(), sizeof(int32_t) * block_jobs.size(), hipMemcpyHostToDevice));
   if (ws_slots > m->sel_ws_cap) {
     if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
     m->d_sel_ws = nullptr; m->sel_ws_cap = 0;
@@ -471,6 +488,7 @@ void free_device(dpllm_model* m) {
   if (m->d_sel_ws_one) (void)hipFree(m->d_sel_ws_one);
   if (m->d_sel_tickets) (void)hipFree(m->d_sel_tickets);
   if (m->d_gemv_jobs) (void)hipFree(m->d_gemv_jobs);
+  if (m->d_block_jobs) (void)hipFree(m->d_block_jobs);
   if (m->d_lane_ws) (void)hipFree(m->d_lane_ws);
   if (m->d_lane_cnt) (void)hipFree(m->d_lane_cnt);
 }
@@ -728,7 +746,8 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
     if (!(parts & DPLLM_STEP_GEMV)) continue;
     for (const GemvLaunch& gl : ph.gemv) {
       if (gl.ka != 0) {
-        launch_fast(gl.mode, gl.ka, gl.kb, m->d_gemv_jobs + gl.first, gl.count, gnone, gl.blocks, st);
+        launch_fast(gl.mode, gl.ka, gl.kb, m->d_gemv_jobs + gl.first, m->d_block_jobs + gl.block_first, gl.count, gnone,
+                    gl.blocks, st);
       } else {
         for (int i = gl.first; i < gl.first + gl.count; ++i) {
           const GemvJob& j = P.gemv_jobs[i];

@@ -508,9 +508,10 @@ __device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, i
 
 // jobs == nullptr: the job passed by value, for njobs right-hand sides in groups of NB that share one pass over
 // the planes (group g reads x + g * NB * in and writes y + g * NB * out; workgroups [g * nblocks, (g + 1) *
-// nblocks) serve it); else (NB = 1) block b belongs to the last job of the table whose block_start <= b
+// nblocks) serve it); else (NB = 1) block b belongs to job block_jobs[b] of the table
 template <int KA, int KB, int NB>
-__global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* __restrict__ jobs, int njobs, GemvJob one) {
+__global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* __restrict__ jobs, const int32_t* __restrict__ block_jobs,
+                                                                 int njobs, GemvJob one) {
   // the tables sit at LDS address 0, which the lookup addresses assume
   __shared__ __attribute__((aligned(16))) char lds[lane_lds_bytes<KA, KB, NB>()];
   if (jobs == nullptr) {
@@ -525,12 +526,7 @@ __global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* 
   }
   if constexpr (NB == 1) {
     const int b = blockIdx.x;
-    int lo = 0, hi = njobs - 1;
-    while (lo < hi) {
-      int mid = (lo + hi + 1) >> 1;
-      if (jobs[mid].block_start <= b) lo = mid; else hi = mid - 1;
-    }
-    GemvJob job = jobs[lo];
+    GemvJob job = jobs[block_jobs[b]];
     gemv_lane_block<KA, KB, 1>(job, b - job.block_start, threadIdx.x, lds);
   }
 }
