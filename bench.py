@@ -250,6 +250,20 @@ def main():
         ms_chain = timed(lambda t: model.dpllm_decode_step(cxp, cyp, k_dev, e_dev), 20, 20)
         chained = {"us_per_step": round(ms_chain * 1e3, 1), "dependent_groups": 4 * args.blocks,
                    "launches_per_step": 8 * args.blocks}
+        # asynchronous estimation (Sec. 5.2): the selectors of the layers fed by the residual stream read the
+        # previous residual vector (q, k, v: the attention output of the block before; gate, up: the block's
+        # input), so they ride in the selector launches of o and down and two of the four groups start with
+        # their GEMV launch
+        for b in range(args.blocks):
+            for j in (0, 1, 2):
+                if b > 0:
+                    model.dpllm_set_selector_input(7 * b + j, cy[7 * (b - 1) + 3])
+            for j in (4, 5):
+                model.dpllm_set_selector_input(7 * b + j, res[b])
+        ms_async = timed(lambda t: model.dpllm_decode_step(cxp, cyp, k_dev, e_dev), 20, 20)
+        chained["us_per_step_async_estimation"] = round(ms_async * 1e3, 1)
+        for i in range(n):
+            model.dpllm_set_selector_input(i, None)
         model.dpllm_decode_step(xs, ys, k_dev, e_dev)   # back to the plan of the headline run
         torch.cuda.synchronize()
 

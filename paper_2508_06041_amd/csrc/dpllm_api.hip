@@ -352,8 +352,10 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   std::vector<int32_t> block_jobs;
   std::vector<size_t> ws_offset;
   size_t ws_slots = 0;
-  int id = 0;
-  while (id < n) {
+  // phases: maximal runs of consecutive linears that do not depend on one another
+  std::vector<std::pair<int, int>> bounds;
+  std::vector<int> phase_of(n, 0);
+  for (int id = 0; id < n;) {
     int end = id + 1;
     for (; end < n; ++end) {  // extend the phase while linear `end` is independent of all of [id, end)
       const Linear& le = m->linears[end];
@@ -368,20 +370,53 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       }
       if (dep) break;
     }
+    for (int j = id; j < end; ++j) phase_of[j] = (int)bounds.size();
+    bounds.emplace_back(id, end);
+    id = end;
+  }
+  // A selector that reads its own input buffer (asynchronous estimation, Sec. 5.2) does not have to run right
+  // before its linear: any phase from which on nothing writes that buffer before the linear runs will do.  It
+  // joins the latest such phase that launches selectors anyway (for linears that estimate from their immediate
+  // input), so that its own phase starts with the GEMV launch; without such a phase it stays where it is.
+  std::vector<char> has_selectors(bounds.size(), 0);
+  for (int j = 0; j < n; ++j)
+    if (!m->linears[j].sel_input) has_selectors[phase_of[j]] = 1;
+  std::vector<std::vector<int>> sel_of_phase(bounds.size());
+  for (int j = 0; j < n; ++j) {
+    const Linear& lin = m->linears[j];
+    int q = phase_of[j];
+    if (lin.sel_input) {
+      int first = q;   // earliest phase the selector may run in
+      while (first > 0) {
+        bool written = false;
+        for (int i = bounds[first - 1].first; i < bounds[first - 1].second && !written; ++i)
+          written = overlap(lin.sel_input, (size_t)lin.L.in * 2, ys[i], (size_t)m->linears[i].L.out * 2);
+        if (written) break;
+        --first;
+      }
+      while (q > first && !has_selectors[q]) --q;
+      if (!has_selectors[q]) q = phase_of[j];
+      has_selectors[q] = 1;
+    }
+    sel_of_phase[q].push_back(j);
+  }
+  for (size_t pi = 0; pi < bounds.size(); ++pi) {
+    const int id = bounds[pi].first, end = bounds[pi].second;
     Phase ph;
     ph.sel_first = (int)sel_jobs.size();
-    ph.sel_count = end - id;
+    ph.sel_count = (int)sel_of_phase[pi].size();
     ph.part_first = (int)sel_parts.size();
     long launch_rowgroups = 0;
-    for (int j = id; j < end; ++j) {
+    for (int j : sel_of_phase[pi]) {
       const Selector& s = m->linears[j].sel[m->linears[j].active];
       launch_rowgroups += sel_rowgroups_of(s.kind, s.r);
     }
-    for (int j = id; j < end; ++j) {
+    for (size_t local = 0; local < sel_of_phase[pi].size(); ++local) {
+      const int j = sel_of_phase[pi][local];
       const Linear& lin = m->linears[j];
       const Selector& s = lin.sel[lin.active];
       SelJob sj = make_sel_job(lin, s, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j, launch_rowgroups);
-      for (int part = 0; part < sj.nparts; ++part) sel_parts.push_back(SelPart{j - id, part});
+      for (int part = 0; part < sj.nparts; ++part) sel_parts.push_back(SelPart{(int)local, part});
       ws_offset.push_back(ws_slots);
       ws_slots += (size_t)sel_slots_of(s.kind, s.r, sj.nchunks);
       sel_jobs.push_back(sj);
@@ -443,7 +478,6 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       ph.gemv.push_back(gl);
     }
     P.phases.push_back(ph);
-    id = end;
   }
   // The tables may still be read by a step enqueued earlier: drain the stream before replacing them.
   HIP_TRY(m, hipStreamSynchronize(st));
@@ -740,8 +774,9 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
   for (const Phase& ph : P.phases) {
     if (parts & DPLLM_STEP_SELECT) {
       const SelJob* jobs = m->d_sel_jobs + ph.sel_first;
-      hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
-                         (const SelPart*)(m->d_sel_parts + ph.part_first), none);
+      if (ph.part_count > 0)
+        hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
+                           (const SelPart*)(m->d_sel_parts + ph.part_first), none);
     }
     if (!(parts & DPLLM_STEP_GEMV)) continue;
     for (const GemvLaunch& gl : ph.gemv) {

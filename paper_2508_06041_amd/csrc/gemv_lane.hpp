@@ -393,14 +393,24 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   constexpr bool kLutAhead = K <= 6;
   LaneTile<K, NB> ring[D];
   LaneLut<K> L;
-  if constexpr (kLutAhead) lane_fetch_lut<K>(L, lut_base, block, lane, wave);
-  int lrb = block, lcc = c0;                   // load cursor
-  // few tiles per row block: their activations are parked once, for every row block of the run
+  // few tiles per row block: their activations are parked once, for every row block of the run.  Their loads
+  // go out first and are parked after the first table rows and tiles have been asked for, so that the
+  // workgroup starts with one memory round trip, not two (k = 4 has no registers to spare for that: there the
+  // tiles are asked for after the activations have been parked)
+  constexpr bool kEarlyX = K != 4;
   const bool keep = NB == 1 && c1 - c0 <= kLaneKeepTiles;
   char* kept = slot + 512;
+  uint32_t xkeep[kLaneKeepTiles];
   if (keep) {
-    for (int cc = c0; cc < c1; ++cc) lane_park_x<K>(lane_load_x(job, cc, lane), lane, slot, kept + (cc - c0) * 256);
+    if constexpr (kEarlyX) {
+#pragma unroll
+      for (int i = 0; i < kLaneKeepTiles; ++i) xkeep[i] = lane_load_x(job, min(c0 + i, job.ncc - 1), lane);
+    } else {
+      for (int cc = c0; cc < c1; ++cc) lane_park_x<K>(lane_load_x(job, cc, lane), lane, slot, kept + (cc - c0) * 256);
+    }
   }
+  if constexpr (kLutAhead) lane_fetch_lut<K>(L, lut_base, block, lane, wave);
+  int lrb = block, lcc = c0;                   // load cursor
   bool more = true;                            // the load cursor is still inside the run
   auto load_next = [&](LaneTile<K, NB>& t) {
     lane_load_tile<K, NB>(t, job, lrb, lcc, lane, !keep, more);
@@ -412,6 +422,11 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   if (!idle) {
 #pragma unroll
     for (int i = 0; i < D - 1; ++i) load_next(ring[i]);
+  }
+  if (kEarlyX && keep) {
+#pragma unroll
+    for (int i = 0; i < kLaneKeepTiles; ++i)
+      if (c0 + i < c1) lane_park_x<K>(xkeep[i], lane, slot, kept + i * 256);
   }
   float acc[NB][4];
 #pragma unroll

@@ -513,3 +513,69 @@ def test_gemv_few_rows_long_columns(dp, out, in_):
             ref = oracle.gemv(synth.planes_np(l["planes"]), k, synth.lut_np(l["luts"][k]), synth.lut_np(X[i]))
             assert rel_l2(ys[i].float().cpu().numpy(), ref) <= REL_L2, (k, i)
     model.close()
+
+
+def test_decode_step_async_selectors_in_chained_blocks(dp):
+    """Two chained blocks (q, k, v, o, gate, up, down) with asynchronous estimation (Sec. 5.2): q, k, v of the
+    second block estimate from the first block's attention output, gate and up from their block's input.  The
+    library runs those selectors in an earlier selector launch than their own group's; every estimate must
+    still come from the buffer named, as it stands when the linear runs, every decision from that estimate,
+    every GEMV from its immediate input at the decided bitwidth.  Checked on the buffers read back."""
+    d, f = 256, 320
+    names = ["q", "k", "v", "o", "gate", "up", "down"]
+    shapes = [(d, d), (d, d), (d, d), (d, d), (f, d), (f, d), (d, f)]
+    nb = 2
+    n = nb * 7
+    model = dp.Model(n)
+    refs = []
+    for i in range(n):
+        out, in_ = shapes[i % 7]
+        lin = synth.make_linear(out, in_, 5, 3, seed=5100 + i)
+        lin["luts"] = {k: (v.float() / 16).half() for k, v in lin["luts"].items()}   # keeps the chain inside fp16 range
+        G = synth.make_G(lin, 3, 4, 32, seed=5200 + i)
+        model.dpllm_load_linear(i, synth.planes_np(lin["planes"]),
+                                {k: synth.lut_np(v) for k, v in lin["luts"].items()}, 3)
+        model.dpllm_set_selector(i, 3, 4, dp.DPLLM_SEL_PROJ, G=G.cuda(), T=float("inf"))
+        refs.append({"planes": synth.planes_np(lin["planes"]), "luts": {k: synth.lut_np(v) for k, v in lin["luts"].items()},
+                     "G": G})
+    res = [torch.zeros(d, dtype=torch.float16, device="cuda") for _ in range(nb + 1)]
+    res[0].copy_(synth.make_x(d, 1, seed=5300)[0])
+    xs, ys, sel_in = [], [], [None] * n
+    for b in range(nb):
+        q, k_, v, o = (torch.zeros(d, dtype=torch.float16, device="cuda") for _ in range(4))
+        g, u = (torch.zeros(f, dtype=torch.float16, device="cuda") for _ in range(2))
+        xs += [res[b], res[b], res[b], v, o, o, g]
+        ys += [q, k_, v, o, g, u, res[b + 1]]
+    for b in range(nb):
+        if b > 0:
+            for j in (0, 1, 2):
+                sel_in[7 * b + j] = ys[7 * (b - 1) + 3]
+        for j in (4, 5):
+            sel_in[7 * b + j] = res[b]
+    k_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(n, dtype=torch.float32, device="cuda")
+
+    def check(T, use_sel):
+        for _ in range(2):   # twice with the same inputs: every buffer holds the value its readers saw
+            model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+        torch.cuda.synchronize()
+        ks, es = k_dev.cpu().numpy(), e_dev.cpu().numpy()
+        for i in range(n):
+            src = sel_in[i] if use_sel and sel_in[i] is not None else xs[i]
+            e_ref = oracle.estimate(synth.lut_np(refs[i]["G"]), synth.lut_np(src))
+            assert math.isclose(float(es[i]), e_ref, rel_tol=3e-7), i
+            assert math.isinf(T[i]) or abs(e_ref - T[i]) > DECISION_BAND * max(abs(T[i]), e_ref)
+            assert int(ks[i]) == oracle.decide(e_ref, T[i], 3, 4), i
+            y_ref = oracle.gemv(refs[i]["planes"], int(ks[i]), refs[i]["luts"][int(ks[i])], synth.lut_np(xs[i]))
+            assert rel_l2(ys[i].float().cpu().numpy(), y_ref) <= REL_L2, i
+        return ks, es
+
+    _, es = check([float("inf")] * n, False)             # immediate inputs, everything at l: the scale of the estimates
+    for i in range(n):
+        model.dpllm_set_selector_input(i, sel_in[i])
+    T = [float(es[i]) * (0.5 if i % 2 else 2.0) for i in range(n)]
+    for i in range(n):
+        model.dpllm_set_selector(i, 3, 4, dp.DPLLM_SEL_PROJ, G=refs[i]["G"].cuda(), T=T[i])
+    ks, _ = check(T, True)
+    assert set(ks.tolist()) == {3, 4}
+    model.close()
