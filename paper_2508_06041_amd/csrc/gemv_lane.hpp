@@ -81,6 +81,18 @@ __device__ __forceinline__ uint32_t lane_entry_addr(uint32_t t, uint32_t lanecol
   return __builtin_amdgcn_perm(t, lanecol, sel);
 }
 
+// The same for an entry byte whose two high bits are not part of the entry number: byte 1 of addr = byte N of t
+// with those bits cleared, in one sub-dword instruction; the other bytes of addr keep what they hold (lane * 4,
+// put there once).  mask: 0x3f in a register.
+template <int N>
+__device__ __forceinline__ void lane_entry_addr_masked(uint32_t t, uint32_t mask, uint32_t& addr) {
+  static_assert(N >= 0 && N < 4, "byte");
+  if constexpr (N == 0) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0 src1_sel:DWORD" : "+v"(addr) : "v"(t), "v"(mask));
+  if constexpr (N == 1) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1 src1_sel:DWORD" : "+v"(addr) : "v"(t), "v"(mask));
+  if constexpr (N == 2) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2 src1_sel:DWORD" : "+v"(addr) : "v"(t), "v"(mask));
+  if constexpr (N == 3) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3 src1_sel:DWORD" : "+v"(addr) : "v"(t), "v"(mask));
+}
+
 __device__ __forceinline__ uint32_t lds_u32(const char* lds, uint32_t addr) { return *reinterpret_cast<const uint32_t*>(lds + addr); }
 
 // ---- a tile: the lane's row, 128 columns, and the lane's dword of the tile's 128 activations -------------------
@@ -137,28 +149,39 @@ __device__ __forceinline__ void lane_park_x(uint32_t x, int lane, char* scratch,
 }
 
 // ---- entry words of one 32-column word -----------------------------------------------------------------------
-// k = 3: four words of four bytes (8 a + b), the pairs (2i, 2i+1), i = 4 jj + n (word 3 is left rotated by
-// one byte: its pair n sits in byte n + 1)
+// k = 3: four words of four bytes (8 a + b) + 64 (two bits of other weights, cleared when the address is formed),
+// the pairs (2i, 2i+1), i = 4 jj + n (word 3 is left rotated by one byte: its pair n sits in byte n + 1)
 __device__ __forceinline__ void lane_entries3(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t (&T)[4]) {
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj) {
-    const uint32_t m0 = rotl_c(0x90909090u, 2 * jj), m1 = rotl_c(0x48484848u, 2 * jj), m2 = rotl_c(0x24242424u, 2 * jj);
-    const uint32_t o = bfi_insn(m0, w0, bfi_insn(m1, w1, w2 & m2));
+    const uint32_t m0 = rotl_c(0x90909090u, 2 * jj), m1 = rotl_c(0x48484848u, 2 * jj);
+    const uint32_t o = bfi_insn(m0, w0, bfi_insn(m1, w1, w2));
     T[jj] = jj == 3 ? o : __builtin_rotateright32(o, 2 * jj + 2);   // jj = 3: a whole byte, taken care of by the byte index
   }
 }
 
 // two-weight schemes: eight lookups from entry words JA, JA + 1 (S: byte shift of word 3, see lane_entries3)
+// k = 3 (S = 1): a[] = eight address registers holding lane * 4, mask = 0x3f
 template <int JA, int S>
-__device__ __forceinline__ void lane_issue_pairs(const uint32_t (&T)[4], uint32_t lanecol, const char* lds, uint32_t (&v)[8]) {
+__device__ __forceinline__ void lane_issue_pairs(const uint32_t (&T)[4], uint32_t lanecol, const char* lds, uint32_t (&v)[8],
+                                                 uint32_t (&a)[8], uint32_t mask) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint32_t t = T[JA + h];
-    if (JA + h == 3 && S == 1) {
-      v[4 * h + 0] = lds_u32(lds, lane_entry_addr<1>(t, lanecol));
-      v[4 * h + 1] = lds_u32(lds, lane_entry_addr<2>(t, lanecol));
-      v[4 * h + 2] = lds_u32(lds, lane_entry_addr<3>(t, lanecol));
-      v[4 * h + 3] = lds_u32(lds, lane_entry_addr<0>(t, lanecol));
+    if constexpr (S == 1) {
+      if (JA + h == 3) {
+        lane_entry_addr_masked<1>(t, mask, a[4 * h + 0]);
+        lane_entry_addr_masked<2>(t, mask, a[4 * h + 1]);
+        lane_entry_addr_masked<3>(t, mask, a[4 * h + 2]);
+        lane_entry_addr_masked<0>(t, mask, a[4 * h + 3]);
+      } else {
+        lane_entry_addr_masked<0>(t, mask, a[4 * h + 0]);
+        lane_entry_addr_masked<1>(t, mask, a[4 * h + 1]);
+        lane_entry_addr_masked<2>(t, mask, a[4 * h + 2]);
+        lane_entry_addr_masked<3>(t, mask, a[4 * h + 3]);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[4 * h + i] = lds_u32(lds, a[4 * h + i]);
     } else {
       v[4 * h + 0] = lds_u32(lds, lane_entry_addr<0>(t, lanecol));
       v[4 * h + 1] = lds_u32(lds, lane_entry_addr<1>(t, lanecol));
@@ -209,7 +232,7 @@ __device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], con
 // xready: the parked activations of sample 0; sample b at + b * xstep
 template <int K, int NB>
 __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t lanecol, int lane, const char* lds, const char* xready,
-                                             int xstep, float (&acc)[NB][4]) {
+                                             int xstep, float (&acc)[NB][4], uint32_t (&addr)[8], uint32_t mask) {
   uint32_t va[8], vb[8];
   u32x4 xq[NB][4];   // xq[b][j][m] = pair 4 q + m of word j of sample b, q = lane mod 4
 #pragma unroll
@@ -227,17 +250,17 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t 
         merge_nibble_pairs(w, T[j]);
       }
     }
-    lane_issue_pairs<0, K == 3>(T[0], lanecol, lds, va);
+    lane_issue_pairs<0, K == 3>(T[0], lanecol, lds, va, addr, mask);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      lane_issue_pairs<2, K == 3>(T[j], lanecol, lds, vb);
+      lane_issue_pairs<2, K == 3>(T[j], lanecol, lds, vb, addr, mask);
       sched_fence();
       {
 #pragma unroll
         for (int b = 0; b < NB; ++b) lane_consume_pairs<0>(va, xq[b][j], acc[b]);
       }
       sched_fence();
-      if (j + 1 < 4) lane_issue_pairs<0, K == 3>(T[j + 1], lanecol, lds, va);
+      if (j + 1 < 4) lane_issue_pairs<0, K == 3>(T[j + 1], lanecol, lds, va, addr, mask);
       sched_fence();
       {
 #pragma unroll
@@ -431,6 +454,9 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   float acc[NB][4];
 #pragma unroll
   for (int b = 0; b < NB; ++b) acc[b][0] = acc[b][1] = acc[b][2] = acc[b][3] = 0.f;
+  uint32_t addr[8], mask = 0x3fu;              // k = 3: address registers of the lookups (see lane_issue_pairs)
+#pragma unroll
+  for (int i = 0; i < 8; ++i) addr[i] = lanecol;
   int rb = block, cc = c0;                     // compute cursor
   auto open_block = [&]() {
     if constexpr (!kLutAhead) lane_fetch_lut<K>(L, lut_base, rb, lane, wave);
@@ -494,7 +520,7 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
         for (int b = 0; b < NB; ++b) lane_park_x<K>(ring[s].x[b], lane, slot + b * 512, slot + b * 512 + 256);
         xready = slot + 256;
       }
-      lane_compute<K, NB>(ring[s], lanecol, lane, lds, xready, 512, acc);
+      lane_compute<K, NB>(ring[s], lanecol, lane, lds, xready, 512, acc, addr, mask);
       if (++cc >= c1) {
         close_block();
         rb += step;
