@@ -249,12 +249,13 @@ int pick_rq_per_block(long total_rq) {
 }
 
 // Row-per-lane arrangement: blocks of 64 rows one workgroup (eight wavefronts) streams.  A workgroup should
-// run for some tens of microseconds (about 384 KiB of planes): shorter ones pay their start-up (tables, first
-// loads) too often, longer ones leave the chip half empty at the end of the launch; and a launch wants at
-// least a few workgroups per compute unit.
+// run for the better part of a hundred microseconds (about 1 MiB of planes): shorter ones pay their start-up
+// (job record, tables, first loads: a few microseconds of an otherwise idle slot) too often, longer ones leave
+// the chip half empty at the end of the launch (measured on the 7B step: 0.25 MiB 496 us, 0.375 MiB 480,
+// 0.75 MiB 471, 1 MiB 468, 2 MiB 477, 4 MiB 546); and a launch wants at least a few workgroups per compute unit.
 int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks) {
   const long bytes_per_block = 64L * L.in * k / 8;
-  long r = std::min<long>(8, std::max<long>(1, 393216 / std::max<long>(1, bytes_per_block)));
+  long r = std::min<long>(16, std::max<long>(1, 1048576 / std::max<long>(1, bytes_per_block)));
   while (r > 1 && total_blocks / r < 1024) --r;
   return (int)r;
 }
