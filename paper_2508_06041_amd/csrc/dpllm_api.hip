@@ -156,7 +156,10 @@ SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* 
   j.nchunks = 1;
   j.chunk_cols = lin.L.in;
   if (s.kind == 1) {
-    const long want = std::min<long>(kSelMaxChunks, 512 / std::max<long>(1, launch_rowgroups));
+    // long rows are cut as well, so that the parts of a launch are of similar size (7B step: 32.5 -> 30.7 us)
+    constexpr long max_cols = 4096;
+    long want = std::min<long>(kSelMaxChunks, 512 / std::max<long>(1, launch_rowgroups));
+    want = std::max<long>(want, std::min<long>(kSelMaxChunks, (lin.L.in + max_cols - 1) / max_cols));
     if (want > 1) {
       j.chunk_cols = (int)((lin.L.in + want - 1) / want + kSelChunkStep - 1) / kSelChunkStep * kSelChunkStep;   // <= want chunks
       j.nchunks = (lin.L.in + j.chunk_cols - 1) / j.chunk_cols;
