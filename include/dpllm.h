@@ -14,12 +14,14 @@
  *     or aborts.  dpllm_last_error() gives the text of the last failure on a model.
  *   - "host" / "device" on a pointer says where the memory lives.  The caller owns all
  *     device memory it passes in (weight arena, G, x, y, k, e) and keeps it alive while
- *     the model refers to it; the library owns only a small selector workspace that
- *     dpllm_model_create allocates and dpllm_model_destroy frees.
+ *     the model refers to it; the library owns only small workspaces (partial results of
+ *     the selectors and of column-split GEMV launches, arrival counters, job tables: a
+ *     few MiB) that dpllm_model_create and the first step allocate and
+ *     dpllm_model_destroy frees.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work
  *     is enqueued on it; only dpllm_load_linear synchronises it.
- *   - One model may be driven from one stream at a time (the selector workspace is
- *     shared by the calls of a model).
+ *   - One model may be driven from one stream at a time (the workspaces are shared by
+ *     the calls of a model; calls that overlap on one model race).
  *   - fp16 values cross the boundary as IEEE binary16 bit patterns (uint16_t).
  *
  * Canonical host layout of a linear with `out` rows and `in` columns (in % 32 == 0):
@@ -117,7 +119,8 @@ int dpllm_set_active_pair(dpllm_model* m, int id, int l, int h);
  * path.  xsel_dev (device fp16 [in], 16-byte aligned, borrowed) replaces the input of linear id's selector in
  * dpllm_decode_step / dpllm_decode_step_parts; the GEMV still reads xs[id].  NULL restores the immediate
  * input.  The step keeps sequential semantics: a selector input written by an earlier linear of the step is
- * read after that linear has run.  Reloading the linear clears it.  Errors: EINVAL, ESTATE. */
+ * read after that linear has run, and when (earlier in the step) such a selector runs is the library's
+ * choice.  Reloading the linear clears it.  Errors: EINVAL, ESTATE. */
 int dpllm_set_selector_input(dpllm_model* m, int id, const void* xsel_dev);
 
 /* "Estimate the relative error for (layer, x)" (Sec. 5.1) and select (Sec. 3):
@@ -145,7 +148,7 @@ int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* 
  * those of running the linears one after another: consecutive linears that do not touch
  * each other's inputs and outputs share launches, dependent ones are ordered on the stream.
  * The first call, and any call after the pointers, selectors or thresholds changed,
- * rebuilds the launch plan (it drains `stream` and copies two small tables); calls with an
+ * rebuilds the launch plan (it drains `stream` and copies a few small tables); calls with an
  * unchanged plan only enqueue kernels.  Errors: EINVAL, ESTATE, ESHAPE, EHIP. */
 int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev,
                       float* e_dev, void* stream);
