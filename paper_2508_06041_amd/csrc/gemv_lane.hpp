@@ -102,12 +102,16 @@ struct LaneTile {
   uint32_t x[NB];
 };
 
-// the lane's dword of the 128 activations of tile cc; columns past the end of a ragged row hold zero codes,
-// whose centroid is not zero: their activations read as 0
+// the lane's dword of the 128 activations of tile cc (address clamped to the row).  Columns past the end of a
+// ragged row hold zero codes, whose centroid is not zero: their activations must read as 0, which lane_mask_x
+// sees to when the value is used.  (Masking right after the load would make the wavefront wait for the load,
+// and with it for every tile load issued before it, at the point of issue.)
 __device__ __forceinline__ uint32_t lane_load_x(const GemvJob& job, int cc, int lane, int sample = 0) {
   const int c = cc * 128 + lane * 2, last = job.ncw * 32 - 2;
-  const uint32_t v = *reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(as_global(job.x) + (size_t)sample * job.ncw * 32 + min(c, last));
-  return c <= last ? v : 0u;
+  return *reinterpret_cast<const DPLLM_GLOBAL uint32_t*>(as_global(job.x) + (size_t)sample * job.ncw * 32 + min(c, last));
+}
+__device__ __forceinline__ uint32_t lane_mask_x(const GemvJob& job, int cc, int lane, uint32_t v) {
+  return cc * 128 + lane * 2 <= job.ncw * 32 - 2 ? v : 0u;
 }
 
 // Loads are never predicated, which keeps the compiler's outstanding-load counts exact.  `real` = false (ring
@@ -430,7 +434,8 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
 #pragma unroll
       for (int i = 0; i < kLaneKeepTiles; ++i) xkeep[i] = lane_load_x(job, min(c0 + i, job.ncc - 1), lane);
     } else {
-      for (int cc = c0; cc < c1; ++cc) lane_park_x<K>(lane_load_x(job, cc, lane), lane, slot, kept + (cc - c0) * 256);
+      for (int cc = c0; cc < c1; ++cc)
+        lane_park_x<K>(lane_mask_x(job, cc, lane, lane_load_x(job, cc, lane)), lane, slot, kept + (cc - c0) * 256);
     }
   }
   if constexpr (kLutAhead) lane_fetch_lut<K>(L, lut_base, block, lane, wave);
@@ -450,7 +455,7 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   if (kEarlyX && keep) {
 #pragma unroll
     for (int i = 0; i < kLaneKeepTiles; ++i)
-      if (c0 + i < c1) lane_park_x<K>(xkeep[i], lane, slot, kept + i * 256);
+      if (c0 + i < c1) lane_park_x<K>(lane_mask_x(job, c0 + i, lane, xkeep[i]), lane, slot, kept + i * 256);
   }
   float acc[NB][4];
 #pragma unroll
@@ -518,7 +523,7 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       const char* xready = kept + (cc - c0) * 256;
       if (!keep) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) lane_park_x<K>(ring[s].x[b], lane, slot + b * 512, slot + b * 512 + 256);
+        for (int b = 0; b < NB; ++b) lane_park_x<K>(lane_mask_x(job, cc, lane, ring[s].x[b]), lane, slot + b * 512, slot + b * 512 + 256);
         xready = slot + 256;
       }
       lane_compute<K, NB>(ring[s], lanecol, lane, lds, xready, 512, acc, addr, mask);
