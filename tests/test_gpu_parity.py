@@ -579,3 +579,25 @@ def test_decode_step_async_selectors_in_chained_blocks(dp):
     ks, _ = check(T, True)
     assert set(ks.tolist()) == {3, 4}
     model.close()
+
+
+@pytest.mark.parametrize("in_,r", [(1056, 17), (11008, 64), (11008, 1024), (32, 3), (16416, 40)])
+def test_estimate_ranks_and_row_lengths(dp, in_, r):
+    """The selector alone over row lengths that are not multiples of a column chunk (512) and ranks that are not
+    multiples of a row group (16), up to the largest rank: a lone selector is cut into row groups x column chunks
+    and the part that finishes last adds up the partial products."""
+    lin = synth.make_linear(4, in_, 4, 3, seed=in_ + r)
+    model = load(dp, [lin])
+    g = torch.Generator().manual_seed(in_ * 7 + r)
+    G = (torch.randn(r, in_, generator=g) / math.sqrt(r)).half()
+    xs = synth.make_x(in_, 3, seed=r)
+    est = [oracle.estimate(synth.lut_np(G), synth.lut_np(x)) for x in xs]
+    T = synth.nudge_threshold(float(np.median(est)), torch.tensor(est))
+    model.dpllm_set_selector(0, 3, 4, dp.DPLLM_SEL_PROJ, G=G.cuda(), T=T)
+    for x, e_ref in zip(xs, est):
+        for _ in range(2):      # the arrival counter is back at zero after a call
+            e, k = model.dpllm_estimate(0, 3, 4, x.cuda())
+            assert math.isclose(float(e), e_ref, rel_tol=3e-7)
+            assert abs(e_ref - T) > DECISION_BAND * max(abs(T), e_ref)
+            assert int(k) == oracle.decide(e_ref, T, 3, 4)
+    model.close()
