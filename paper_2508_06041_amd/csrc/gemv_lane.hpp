@@ -485,13 +485,17 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       if (nsplit > 1) {
         // every workgroup of the row block leaves its sums, then takes a ticket; the holder of the last ticket
         // finds all of them, adds them in the order of the splits and leaves the counter at zero again.  The sums
-        // travel as device-scope atomic stores and loads, which pass through the per-die caches by themselves:
-        // waiting for the store to be acknowledged before taking the ticket orders them, and no cache has to be
-        // written back or invalidated as a whole (what a device-scope fence would do, at several times the cost
-        // of the launch)
+        // are left with device-scope atomic exchanges and read with device-scope atomic loads: a read-modify-write
+        // is carried out where all dies see it, like the ticket itself, and has been carried out when its old
+        // value is back, so taking the ticket after that orders the two without writing back or invalidating a
+        // whole per-die cache (what a device-scope fence does, at several times the cost of the launch).  A
+        // store, atomic or not, is not enough: it is acknowledged before other dies see it (measured: under the
+        // memory traffic of concurrent GEMV workgroups one estimate in a few hundred came out with a stale sum).
         DPLLM_GLOBAL float* part = as_global(job.ws) + (size_t)(rb * NB + wave) * nsplit * 64 + lane;
         DPLLM_GLOBAL uint32_t* ticket = as_global(job.cnt) + rb * NB + wave;
-        __hip_atomic_store(part + split * 64, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t before = __hip_atomic_exchange(reinterpret_cast<DPLLM_GLOBAL uint32_t*>(part + split * 64),
+                                                      __builtin_bit_cast(uint32_t, s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("" ::"v"(before));   // the old value is waited for: the exchange has been carried out
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         uint32_t old = 0;
         if (lane == 0) old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -171,16 +171,25 @@ __device__ __forceinline__ void selector_part(const SelJob& job, int part, int t
       ca = ca + kSelChunkStep >= cb + nit * kSelChunkStep ? ca + kSelChunkStep - nit * kSelChunkStep : ca + kSelChunkStep;
     }
   }
-  // The partial products travel as device-scope atomic stores and loads (they pass the per-die caches by
-  // themselves); every store is acknowledged before the ticket is taken, so whoever draws the last ticket
-  // finds all of them.
+  // The partial products are left with device-scope atomic exchanges and read with device-scope atomic loads.
+  // A read-modify-write is carried out where all dies see it, like the ticket itself, and has been carried out
+  // when its old value is back; a store, atomic or not, is acknowledged before other dies see it.  So every
+  // exchange is waited for before the ticket is taken, and whoever draws the last ticket finds all of them.
   const int nrows = sel_rowgroups_of(1, job.r) * kSelPartRows;
   DPLLM_SEL_GLOBAL double* ws = (DPLLM_SEL_GLOBAL double*)job.ws;
   DPLLM_SEL_GLOBAL uint32_t* ticket = (DPLLM_SEL_GLOBAL uint32_t*)job.ticket;
+  double rowsum[kSelRowsPerWave];
 #pragma unroll
-  for (int i = 0; i < kSelRowsPerWave; ++i) {
-    const double v = wave_sum_f64(acc[i]);
-    if (lane == 0) __hip_atomic_store(ws + (size_t)ch * nrows + row0 + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int i = 0; i < kSelRowsPerWave; ++i) rowsum[i] = wave_sum_f64(acc[i]);
+  if (lane == 0) {   // four exchanges in flight, one wait for their old values
+    unsigned long long before[kSelRowsPerWave];
+#pragma unroll
+    for (int i = 0; i < kSelRowsPerWave; ++i)
+      before[i] = __hip_atomic_exchange((DPLLM_SEL_GLOBAL unsigned long long*)(ws + (size_t)ch * nrows + row0 + i),
+                                        __builtin_bit_cast(unsigned long long, rowsum[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    static_assert(kSelRowsPerWave == 4, "the wait below names four values");
+    asm volatile("" ::"v"((uint32_t)before[0]), "v"((uint32_t)(before[0] >> 32)), "v"((uint32_t)before[1]), "v"((uint32_t)(before[1] >> 32)),
+                 "v"((uint32_t)before[2]), "v"((uint32_t)(before[2] >> 32)), "v"((uint32_t)before[3]), "v"((uint32_t)(before[3] >> 32)));
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();

@@ -87,6 +87,27 @@ def test_decode_step_llama7b_full(dp):
     model, meta = bench.build_model(dp, synth, torch, synth.LLAMA_7B, 32, 8, 3, 4, 8, seed=4321, keep_blocks=(0,))
     seen = run_step_checks(dp, model, meta, 3, 4, steps=[0, 3, 7])
     assert seen == {3, 4}
+    # The parts of a selector hand their partial sums over inside one launch; the same step repeated must give
+    # the same bits every time, also while other launches keep the memory system busy (a hand-over that is not
+    # ordered shows up as a stale partial sum once in a few hundred estimates).
+    n_all = len(meta["shapes"])
+    xs_r = [meta["xs_by_in"][in_][5].contiguous() for _, in_ in meta["shapes"]]
+    ys_r = [torch.empty(out, dtype=torch.float16, device="cuda") for out, _ in meta["shapes"]]
+    k_r = torch.zeros(n_all, dtype=torch.int32, device="cuda")
+    e_r = torch.zeros(n_all, dtype=torch.float32, device="cuda")
+    other = torch.cuda.Stream()
+    big = torch.ones(1 << 27, dtype=torch.int32, device="cuda")
+    first = None
+    for rep in range(40):
+        with torch.cuda.stream(other):     # unrelated traffic next to the step
+            big.add_(1)
+        model.dpllm_decode_step(xs_r, ys_r, k_r, e_r)
+        torch.cuda.synchronize()
+        now = (k_r.clone(), e_r.clone(), ys_r[6].clone(), ys_r[-1].clone())
+        if first is None:
+            first = now
+        assert all(torch.equal(a, b) for a, b in zip(first, now)), rep
+    del big
     # every bitwidth pinned for all layers (the +/-inf protocol of the latency runs): the streaming launch
     # (several row quads per wavefront) against the oracle on block 0 and against single launches elsewhere
     shapes = meta["shapes"]
