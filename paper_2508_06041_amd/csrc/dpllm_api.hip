@@ -83,7 +83,7 @@ struct dpllm_model {
   std::vector<Linear> linears;
   std::string err;
   uint64_t version = 1;            // bumped by every call that changes what a plan depends on
-  int layout = kLayoutRowQuad;     // arrangement given to linears loaded from now on
+  int layout = kLayoutRowLane;     // arrangement given to linears loaded from now on
   // decode-step plan and its device tables
   StepPlan plan;
   SelJob* d_sel_jobs = nullptr;
