@@ -80,7 +80,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--blocks", type=int, default=32, help="Transformer blocks (32 = the 7B shape)")
+    ap.add_argument("--model", choices=["7b", "8b", "70b"], default="7b",
+                    help="shape of the linears: Llama-7B (the headline workload), Llama-3-8B, or 70B with p = 6 planes")
+    ap.add_argument("--blocks", type=int, default=None, help="Transformer blocks (default: 32 for 7b and 8b, 80 for 70b)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-k sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only (no HIP graph replay)")
@@ -113,7 +115,12 @@ def main():
             dp.dpllm_debug_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
-    shapes, p, l, h, n_x = synth.LLAMA_7B, 8, 3, 4, 256
+    shapes, p = {"7b": (synth.LLAMA_7B, 8), "8b": (synth.LLAMA3_8B, 8), "70b": (synth.LLAMA_70B, 6)}[args.model]
+    l, h, n_x = 3, 4, 256
+    if args.blocks is None:
+        args.blocks = 80 if args.model == "70b" else 32
+    if args.model == "70b":
+        n_x = 32   # the calibration pass over the activations is what takes time at this size
     layout = dp.DPLLM_LAYOUT_ROWLANE if args.layout == "rowlane" else dp.DPLLM_LAYOUT_ROWQUAD
     model, meta = build_model(dp, synth, torch, shapes, args.blocks, p, l, h, n_x, log=log, layout=layout)
     gemv_name = "gemv_lane_kernel<3,4,1>" if args.layout == "rowlane" else "gemv_kernel<3,4,1>"
@@ -207,7 +214,7 @@ def main():
     # scaled by a plain copy kernel); it belongs to the default 32-block workload only
     traffic = None
     counters = os.path.join(ROOT, "profiles", "decode_step_7b_hbm_counters.txt")
-    if args.blocks == 32 and os.path.exists(counters):
+    if args.model == "7b" and args.blocks == 32 and os.path.exists(counters):
         for line in open(counters):
             if line.startswith("gemv_traffic_bytes_per_launch"):
                 traffic = float(line.split()[1])
@@ -239,7 +246,7 @@ def main():
     # writes the next residual): four dependent groups per block, each a selector launch and a GEMV launch of a
     # few linears.  Reported beside the headline figure, which runs all linears of the step as one group.
     chained = None
-    if args.chained and [name for name, _, _ in shapes] == ["q", "k", "v", "o", "gate", "up", "down"]:
+    if args.chained and all(shapes[i][1:] == shapes[0][1:] and shapes[0][1] == shapes[0][2] for i in range(4)):   # q, k, v, o square and alike
         d, f = shapes[0][2], shapes[4][1]
         res = [torch.zeros(d, dtype=torch.float16, device="cuda") for _ in range(args.blocks + 1)]
         res[0].copy_(meta["xs_by_in"][d][0] / 1024)
@@ -302,9 +309,9 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "Llama-7B-shaped decode step: %d blocks x 7 linears, p=8 bitplanes, (l,h)=(3,4), "
+        "config": {"workload": "Llama-%s-shaped decode step: %d blocks x 7 linears, p=%d bitplanes, (l,h)=(3,4), "
                                "rank-64 projection selectors, thresholds tau~U[0.05,0.3] x median||W_h x||, "
-                               "256 outlier-fp16 activation vectors, batch 1" % args.blocks,
+                               "%d outlier-fp16 activation vectors, batch 1" % (args.model.upper(), args.blocks, p, n_x),
                    "linears": n, "layout": args.layout, "frac_of_hbm_peak": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "us_per_decode_step": round(ms_step * 1e3, 1),
         "us_per_decode_step_eager": round(ms_step_eager * 1e3, 1),
