@@ -256,9 +256,10 @@ int pick_rq_per_block(long total_rq) {
 // (job record, tables, first loads: a few microseconds of an otherwise idle slot) too often, longer ones leave
 // the chip half empty at the end of the launch (measured on the 7B step: 0.25 MiB 496 us, 0.375 MiB 480,
 // 0.75 MiB 471, 1 MiB 468, 2 MiB 477, 4 MiB 546); and a launch wants at least a few workgroups per compute unit.
-int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks) {
+constexpr long kLaneGroupBytes = 1048576;
+int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks, long group_bytes = kLaneGroupBytes) {
   const long bytes_per_block = 64L * L.in * k / 8;
-  long r = std::min<long>(16, std::max<long>(1, 1048576 / std::max<long>(1, bytes_per_block)));
+  long r = std::min<long>(16, std::max<long>(1, group_bytes / std::max<long>(1, bytes_per_block)));
   while (r > 1 && total_blocks / r < 1024) --r;
   return (int)r;
 }
@@ -455,6 +456,20 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
             const int rpb = pick_blocks_per_group(L, c.kb, total_rq);
             lane_groups += (L.nrq + rpb - 1) / rpb;
           }
+      std::vector<long> bytes_after(end - id, 0);   // plane bytes of the launch that follow linear j
+      {
+        long acc = 0;
+        for (int j = end - 1; j >= id; --j) {
+          if (!(cls_of(j) == c)) continue;
+          bytes_after[j - id] = acc;
+          const LinearLayout& L = m->linears[j].L;
+          acc += (long)L.nrq * 64 * L.in * (c.ka + c.kb) / 16;
+        }
+      }
+      // Large launches: the linears dispatched last (one round of workgroups: two on each of 256 compute units)
+      // get workgroups of half the usual work, so that the chip drains in less time at the end of the launch
+      // (measured on the 7B step: 0.5 - 0.8 % of the launch; quarters and eighths did not add to that).
+      const bool taper = c.mode == kLayoutRowLane && lane_groups >= 2048;
       long pool_used = 0;
       int blocks = 0;
       for (int j = id; j < end; ++j) {
@@ -462,7 +477,9 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
         const Linear& lin = m->linears[j];
         const Selector& s = lin.sel[lin.active];
         GemvJob gj = make_gemv_job(lin, s.l, s.h, s.l == s.h ? nullptr : k_dev + j, xs[j], ys[j]);
-        const int rpb = c.mode == kLayoutRowLane ? pick_blocks_per_group(lin.L, s.h, total_rq) : rpb_quad;
+        long group_bytes = kLaneGroupBytes;
+        if (taper && bytes_after[j - id] < 512 * kLaneGroupBytes) group_bytes /= 2;
+        const int rpb = c.mode == kLayoutRowLane ? pick_blocks_per_group(lin.L, s.h, total_rq, group_bytes) : rpb_quad;
         gj.nblocks = (lin.L.nrq + rpb - 1) / rpb;
         if (c.mode == kLayoutRowLane) {
           gj.nsplit = pick_lane_split(lin.L, lane_groups, lin.L.nrq, kLanePoolRows - pool_used);
