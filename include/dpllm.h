@@ -13,15 +13,21 @@
  *   - Every function returns DPLLM_OK (0) or a negative DPLLM_E* code; nothing throws
  *     or aborts.  dpllm_last_error() gives the text of the last failure on a model.
  *   - "host" / "device" on a pointer says where the memory lives.  The caller owns all
- *     device memory it passes in (weight arena, G, x, y, k, e) and keeps it alive while
- *     the model refers to it; the library owns only small workspaces (partial results of
- *     the selectors and of column-split GEMV launches, arrival counters, job tables: a
- *     few MiB) that dpllm_model_create and the first step allocate and
- *     dpllm_model_destroy frees.
+ *     device memory: the weight arenas, G, x, y, k, e, and one workspace per model
+ *     (partial results of the selectors and of column-split GEMV launches, arrival
+ *     counters, job and parameter tables: a few MiB, see dpllm_workspace_bytes) that it
+ *     hands over with dpllm_set_workspace.  Everything is borrowed until the model is
+ *     destroyed (a linear's memory: until it is loaded again).  No call allocates device
+ *     memory, except dpllm_load_linear from host pointers (a staging buffer it frees
+ *     before it returns).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work
  *     is enqueued on it; only dpllm_load_linear synchronises it.
- *   - One model may be driven from one stream at a time (the workspaces are shared by
- *     the calls of a model; calls that overlap on one model race).
+ *   - One model may be driven from one stream at a time (the workspace is shared by
+ *     the calls of a model; calls that overlap on one model race).  The calls that
+ *     configure a model (load, set_selector, set_threshold, set_active_pair,
+ *     set_target_entry, set_selector_input, set_workspace) take effect for the work
+ *     enqueued after them and must not run while a step of the model is being captured
+ *     into a graph; dpllm_set_target is the call for switching while steps are in flight.
  *   - fp16 values cross the boundary as IEEE binary16 bit patterns (uint16_t).
  *
  * Canonical host layout of a linear with `out` rows and `in` columns (in % 32 == 0):
@@ -52,6 +58,7 @@ extern "C" {
 #define DPLLM_MAX_BITS 8
 #define DPLLM_MAX_BATCH 8
 #define DPLLM_MAX_PAIRS 8   /* (l,h) candidate pairs kept per linear                    */
+#define DPLLM_MAX_TARGETS 8 /* target precisions (sets of pairs and thresholds) resident */
 #define DPLLM_MAX_RANK 1024 /* projection rank r                                        */
 
 #define DPLLM_SEL_NONE 0   /* no estimator: always l                                     */
@@ -71,19 +78,7 @@ void dpllm_model_destroy(dpllm_model* m);
 /* Text of the last error on m (owned by m, valid until the next failing call). */
 const char* dpllm_last_error(const dpllm_model* m);
 
-/* Private arrangement of the planes given to linears loaded after the call (both serve every entry point
- * with identical results up to summation order):
- *   DPLLM_LAYOUT_ROWLANE (default): a lane owns one row; table lookups are free of LDS bank conflicts; work
- *     items are blocks of 64 rows (split by columns when a launch has few of them).  The faster one for whole
- *     decode steps (by about 20 % on 7B-, 8B- and 70B-shaped steps) and for small batches;
- *   DPLLM_LAYOUT_ROWQUAD: a lane owns 4 rows x 32 columns; a launch is cut into many small work items, which
- *     makes a lone dpllm_gemv call on one linear a few microseconds faster.
- * Errors: EINVAL. */
-#define DPLLM_LAYOUT_ROWQUAD 0
-#define DPLLM_LAYOUT_ROWLANE 1
-int dpllm_model_set_layout(dpllm_model* m, int layout);
-
-/* Bytes of device arena one linear needs (planes + tables, 256-byte aligned parts; enough for either layout).
+/* Bytes of device arena one linear needs (planes + tables, 256-byte aligned parts).
  * Errors: EINVAL (bytes NULL), ESHAPE, ERANGE. */
 int dpllm_linear_device_bytes(int out, int in, int p, int kmin, size_t* bytes);
 
@@ -98,22 +93,49 @@ int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin,
                       const uint32_t* planes, const uint16_t* const* luts, int src_on_device,
                       void* dev_arena, size_t arena_bytes, void* stream);
 
+/* Bytes of workspace the model needs as it stands (linears loaded, pairs set): enough for every entry point and
+ * every order of the linears' buffers.  Ask again after loading more linears or attaching pairs of higher rank.
+ * Errors: EINVAL. */
+int dpllm_workspace_bytes(const dpllm_model* m, size_t* bytes);
+
+/* Hands the model its workspace: ws_dev (device, caller-owned, 256-byte aligned, >= dpllm_workspace_bytes), which
+ * the model uses until it is destroyed or given another.  Enqueues the clearing of its counters on `stream`.
+ * dpllm_estimate, dpllm_decode_step(_parts) and dpllm_set_target need a workspace; dpllm_gemv runs without one
+ * (it then never splits the columns of a linear over several workgroups).
+ * Errors: EINVAL, ESTATE (too small), EHIP. */
+int dpllm_set_workspace(dpllm_model* m, void* ws_dev, size_t bytes, void* stream);
+
 /* Attaches the precision selector of candidate pair (l, h), kmin <= l <= h <= p, to a
  * loaded linear and makes it the active pair (Sec. 3: two candidate precisions per
  * layer; Sec. 5.1: one G per pair).  kind = DPLLM_SEL_PROJ: G_dev is a device pointer
  * to fp16 [r][in] (row-major, borrowed), G = A (W_h - W_l) precomputed by the caller,
  * 1 <= r <= DPLLM_MAX_RANK.  kind = DPLLM_SEL_LINREG uses alpha, beta.  kind =
  * DPLLM_SEL_NONE needs l == h.  T may be +inf (always l) or -inf (always h), not NaN.
- * Setting an existing pair replaces it.  Errors: EINVAL, ERANGE, ESTATE. */
+ * Setting an existing pair replaces it.  The pair becomes the linear's pair under target 0.
+ * Errors: EINVAL, ERANGE, ESTATE. */
 int dpllm_set_selector(dpllm_model* m, int id, int l, int h, int kind, const void* G_dev, int r,
                        float alpha, float beta, float T);
 
-/* Replaces the threshold of an existing pair (Algorithm 1: one threshold list per
- * target precision).  Errors: EINVAL (NaN), ESTATE (pair not set). */
+/* Replaces the threshold an existing pair has under target 0 and in dpllm_estimate.
+ * Errors: EINVAL (NaN), ESTATE (pair not set). */
 int dpllm_set_threshold(dpllm_model* m, int id, int l, int h, float T);
 
-/* Chooses which of a linear's pairs dpllm_decode_step uses.  Errors: ESTATE. */
+/* Chooses which of a linear's pairs is its pair under target 0.  Errors: ESTATE. */
 int dpllm_set_active_pair(dpllm_model* m, int id, int l, int h);
+
+/* Run-time adaptation (Sec. 2.1: the target precision changes from query to query; Algorithm 1: one threshold
+ * list per target precision; Sec. 5.1: one G per candidate pair, all resident).  A model holds
+ * DPLLM_MAX_TARGETS targets.  Target 0 is what dpllm_set_selector / dpllm_set_threshold / dpllm_set_active_pair
+ * describe.  dpllm_set_target_entry says that under target t (1 <= t < DPLLM_MAX_TARGETS) linear id runs pair
+ * (l, h), which must have been attached with dpllm_set_selector, with threshold T; a linear without an entry
+ * for t runs as under target 0.  Errors: EINVAL, ESTATE (pair not set). */
+int dpllm_set_target_entry(dpllm_model* m, int target, int id, int l, int h, float T);
+
+/* Switches the whole model to `target` with one word written on the device, enqueued on `stream`: the steps
+ * enqueued behind it (also replays of graphs captured earlier, and it can be captured itself) run every linear
+ * under that target's pair and threshold.  No launch plan is rebuilt and nothing is synchronised.
+ * Errors: EINVAL, ESTATE (no workspace), EHIP. */
+int dpllm_set_target(dpllm_model* m, int target, void* stream);
 
 /* Asynchronous estimation (Sec. 5.2): the selector of a layer fed by the residual stream may read the
  * previous residual vector instead of the layer's immediate input, which takes the estimate off the critical
@@ -126,31 +148,37 @@ int dpllm_set_selector_input(dpllm_model* m, int id, const void* xsel_dev);
 
 /* "Estimate the relative error for (layer, x)" (Sec. 5.1) and select (Sec. 3):
  * e_dev[0] = estimate (fp32, rounded from the fp64 the decision is taken in),
- * k_dev[0] = h if estimate > T else l.  x_dev: device fp16 [in].  e_dev, k_dev: device.
- * Errors: EINVAL, ESTATE (pair not set), EHIP. */
+ * k_dev[0] = h if estimate > T else l, for pair (l, h) of the linear and the threshold it has under target 0.
+ * x_dev: device fp16 [in].  e_dev, k_dev: device.
+ * Errors: EINVAL, ESTATE (pair not set, no workspace), EHIP. */
 int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, float* e_dev,
                    int32_t* k_dev, void* stream);
 
 /* "Run the GEMV at bitwidth k": y[b][o] = sum_c LUT_k[o][code_k(o,c)] * x[b][c], fp32
  * accumulation, fp16 result.  k >= 0: that bitwidth.  k < 0: the bitwidth is read on the
- * device from k_dev[0], which must hold l or h of the linear's active pair (the hand-over
- * from dpllm_estimate without a host round trip).  x_dev: device fp16 [B][in]; y_dev:
- * device fp16 [B][out]; 1 <= B <= DPLLM_MAX_BATCH; one bitwidth serves the whole batch.
+ * device from k_dev[0] (the hand-over from dpllm_estimate without a host round trip); a
+ * value there that the linear does not serve (outside [kmin, p]) leaves y_dev untouched.
+ * x_dev: device fp16 [B][in]; y_dev: device fp16 [B][out], not overlapping x_dev;
+ * 1 <= B <= DPLLM_MAX_BATCH; one bitwidth serves the whole batch.
  * Errors: EINVAL, ESHAPE, ERANGE, ESTATE, EHIP. */
 int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* x_dev, void* y_dev,
                int B, void* stream);
 
 /* "Run a whole decode step under per-layer thresholds" (Sec. 3, every linear operation
  * of every Transformer block carries a selector): for id = 0..n_linears-1 in order,
- * estimate on xs[id] with the active pair, then the GEMV at the selected bitwidth into
- * ys[id], batch 1, all on `stream` with no host synchronisation.  xs, ys: host arrays of
- * n_linears device pointers (fp16 [in_id], fp16 [out_id]).  k_dev, e_dev: device arrays
- * of n_linears entries receiving every linear's bitwidth and estimate.  Results equal
- * those of running the linears one after another: consecutive linears that do not touch
- * each other's inputs and outputs share launches, dependent ones are ordered on the stream.
- * The first call, and any call after the pointers, selectors or thresholds changed,
- * rebuilds the launch plan (it drains `stream` and copies a few small tables); calls with an
- * unchanged plan only enqueue kernels.  Errors: EINVAL, ESTATE, ESHAPE, EHIP. */
+ * estimate on xs[id] with the linear's pair and threshold under the active target, then
+ * the GEMV at the selected bitwidth into ys[id], batch 1, all on `stream` with no host
+ * synchronisation.  xs, ys: host arrays of n_linears device pointers (fp16 [in_id], fp16
+ * [out_id]; xs[id] and ys[id] must not overlap).  k_dev, e_dev: device arrays of n_linears
+ * entries receiving every linear's bitwidth and estimate.  Results equal those of running
+ * the linears one after another: consecutive linears that do not touch each other's
+ * inputs and outputs share launches, dependent ones are ordered on the stream.
+ * The first call, and a call after the pointers, the linears or the shapes of their pairs
+ * changed, rebuilds the launch plan and copies its tables into the workspace; a call after
+ * thresholds, pairs in use or target entries changed copies the parameter table.  Both are
+ * asynchronous copies on `stream` (nothing is synchronised, nothing allocated) but cannot
+ * be captured into a graph: ESTATE then.  Every other call only enqueues kernels.
+ * Errors: EINVAL, ESTATE, ESHAPE, EHIP. */
 int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev,
                       float* e_dev, void* stream);
 

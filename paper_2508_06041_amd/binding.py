@@ -14,11 +14,14 @@ _LIB_PATH = os.path.join(_HERE, "libdpllm.so")
 DPLLM_OK, DPLLM_EINVAL, DPLLM_ESHAPE, DPLLM_ERANGE, DPLLM_ESTATE, DPLLM_EHIP = 0, -1, -2, -3, -4, -5
 DPLLM_SEL_NONE, DPLLM_SEL_PROJ, DPLLM_SEL_LINREG = 0, 1, 2
 DPLLM_MAX_BATCH = 8
+DPLLM_MAX_PAIRS = 8
+DPLLM_MAX_TARGETS = 8
 DPLLM_STEP_SELECT, DPLLM_STEP_GEMV = 1, 2
-DPLLM_LAYOUT_ROWQUAD, DPLLM_LAYOUT_ROWLANE = 0, 1
 
 SYMBOLS = ["dpllm_model_create", "dpllm_model_destroy", "dpllm_last_error", "dpllm_linear_device_bytes",
-           "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair", "dpllm_set_selector_input", "dpllm_model_set_layout",
+           "dpllm_workspace_bytes", "dpllm_set_workspace",
+           "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair",
+           "dpllm_set_target_entry", "dpllm_set_target", "dpllm_set_selector_input",
            "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_copy", "dpllm_debug_read"]
 
 
@@ -45,7 +48,10 @@ def _load():
     L.dpllm_set_threshold.argtypes = [vp, i32, i32, i32, f32]
     L.dpllm_set_active_pair.argtypes = [vp, i32, i32, i32]
     L.dpllm_set_selector_input.argtypes = [vp, i32, vp]
-    L.dpllm_model_set_layout.argtypes = [vp, i32]
+    L.dpllm_workspace_bytes.argtypes = [vp, C.POINTER(sz)]
+    L.dpllm_set_workspace.argtypes = [vp, vp, sz, vp]
+    L.dpllm_set_target_entry.argtypes = [vp, i32, i32, i32, i32, f32]
+    L.dpllm_set_target.argtypes = [vp, i32, vp]
     L.dpllm_estimate.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
     L.dpllm_gemv.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp]
     L.dpllm_decode_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
@@ -98,23 +104,44 @@ def dpllm_debug_read(src, sink):
 
 
 class Model:
-    """Owns the C handle and the torch tensors used as device arenas."""
+    """Owns the C handle and the torch tensors used as device memory (arenas, workspace)."""
 
-    def __init__(self, n_linears, layout=None):
+    def __init__(self, n_linears):
         h = C.c_void_p()
         rc = lib.dpllm_model_create(C.byref(h), n_linears)
         if rc != 0:
             raise DpllmError(rc, "dpllm_model_create")
         self.h = h
-        if layout is None and os.environ.get("DPLLM_LAYOUT"):
-            layout = {"rowquad": 0, "rowlane": 1}[os.environ["DPLLM_LAYOUT"]]
-        if layout is not None:
-            _check(self.h, lib.dpllm_model_set_layout(self.h, layout))
         self.n = n_linears
         self.arenas = {}
         self.keep = {}
         self.shapes = {}
         self._sel_inputs = {}
+        self.workspace = None
+        self._ws_stale = True      # the model changed in a way that may ask for a larger workspace
+
+    def dpllm_workspace_bytes(self):
+        n = C.c_size_t(0)
+        _check(self.h, lib.dpllm_workspace_bytes(self.h, C.byref(n)))
+        return n.value
+
+    def dpllm_set_workspace(self, tensor=None):
+        """Hands the model a workspace: `tensor` (device, uint8) or a fresh allocation of the size the model asks
+        for.  The calls that need one allocate it on first use; call this yourself to choose the moment."""
+        need = self.dpllm_workspace_bytes()
+        if tensor is None:
+            tensor = torch.empty(need, dtype=torch.uint8, device="cuda")
+        _check(self.h, lib.dpllm_set_workspace(self.h, _ptr(tensor), tensor.numel() * tensor.element_size(), _stream()))
+        old, self.workspace = self.workspace, tensor
+        self._ws_stale = False
+        return old   # the caller decides when the previous one may go (work enqueued earlier may still use it)
+
+    def _need_workspace(self):
+        if self._ws_stale and (self.workspace is None or self.workspace.numel() < self.dpllm_workspace_bytes()):
+            old = self.dpllm_set_workspace()
+            if old is not None:
+                torch.cuda.current_stream().synchronize()
+        self._ws_stale = False
 
     def close(self):
         if self.h:
@@ -145,6 +172,7 @@ class Model:
         _check(self.h, rc)
         self.arenas[id] = arena
         self.shapes[id] = (out, nw * 32, p, kmin)
+        self._ws_stale = True
 
     def dpllm_set_selector(self, id, l, h, kind, G=None, alpha=0.0, beta=0.0, T=float("inf")):
         r = 0
@@ -154,12 +182,20 @@ class Model:
             r = G.shape[0]
             self.keep[(id, l, h)] = G
         _check(self.h, lib.dpllm_set_selector(self.h, id, l, h, kind, _ptr(G), r, alpha, beta, T))
+        self._ws_stale = True
 
     def dpllm_set_threshold(self, id, l, h, T):
         _check(self.h, lib.dpllm_set_threshold(self.h, id, l, h, T))
 
     def dpllm_set_active_pair(self, id, l, h):
         _check(self.h, lib.dpllm_set_active_pair(self.h, id, l, h))
+
+    def dpllm_set_target_entry(self, target, id, l, h, T):
+        _check(self.h, lib.dpllm_set_target_entry(self.h, target, id, l, h, T))
+
+    def dpllm_set_target(self, target):
+        self._need_workspace()
+        _check(self.h, lib.dpllm_set_target(self.h, target, _stream()))
 
     def dpllm_set_selector_input(self, id, x_sel):
         """x_sel: device fp16 [in] the selector of linear id reads in the step calls (None: its immediate input).
@@ -170,6 +206,7 @@ class Model:
     def dpllm_estimate(self, id, l, h, x, e_out=None, k_out=None):
         e_out = torch.empty(1, dtype=torch.float32, device="cuda") if e_out is None else e_out
         k_out = torch.empty(1, dtype=torch.int32, device="cuda") if k_out is None else k_out
+        self._need_workspace()
         _check(self.h, lib.dpllm_estimate(self.h, id, l, h, _ptr(x), _ptr(e_out), _ptr(k_out), _stream()))
         return e_out, k_out
 
@@ -179,6 +216,7 @@ class Model:
         B = 1 if x.dim() == 1 else x.shape[0]
         if y is None:
             y = torch.empty((out,) if x.dim() == 1 else (B, out), dtype=torch.float16, device="cuda")
+        self._need_workspace()
         _check(self.h, lib.dpllm_gemv(self.h, id, k, _ptr(k_dev), _ptr(x), _ptr(y), B, _stream()))
         return y
 
@@ -191,10 +229,12 @@ class Model:
         return (C.c_void_p * self.n)(*[t.data_ptr() for t in tensors])
 
     def dpllm_decode_step(self, xs, ys, k_out, e_out):
+        self._need_workspace()
         _check(self.h, lib.dpllm_decode_step(self.h, self.pointers(xs), self.pointers(ys), _ptr(k_out), _ptr(e_out),
                                              _stream()))
 
     def dpllm_decode_step_parts(self, xs, ys, k_out, e_out, parts):
+        self._need_workspace()
         _check(self.h, lib.dpllm_decode_step_parts(self.h, self.pointers(xs), self.pointers(ys), _ptr(k_out),
                                                    _ptr(e_out), parts, _stream()))
 

@@ -11,37 +11,27 @@ namespace dpllm {
 
 __device__ __forceinline__ uint32_t rotr32(uint32_t v, int s) { return __builtin_rotateright32(v, s); }
 
-// canonical planes [p][out][ncw] -> device planes; one thread per (plane, row group, column word / tile):
-// it writes one 128-bit value (row quad: 4 rows x 1 word; row per lane: 1 row x 4 words)
+// canonical planes [p][out][ncw] -> device planes; one thread per (plane, block of 64 rows, tile, row): it
+// writes one 128-bit value (1 row x 4 words)
 __global__ void retile_planes_kernel(const uint32_t* __restrict__ canon, uint4* __restrict__ dev,
-                                     int p, int out, int ncw, int ncc, int nrq, int row_lane, size_t plane_stride_u4) {
-  const size_t per_plane = row_lane ? (size_t)nrq * ncc * 64 : (size_t)nrq * ncw;
+                                     int p, int out, int ncw, int ncc, int nrq, size_t plane_stride_u4) {
+  const size_t per_plane = (size_t)nrq * ncc * 64;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= per_plane * p) return;
   int b = (int)(i / per_plane);
   size_t e = i % per_plane;
   uint32_t w[4];
-  if (row_lane) {
-    const int o = (int)(e / ((size_t)ncc * 64)) * 64 + (int)(e % 64), cc = (int)(e / 64 % ncc);
+  const int o = (int)(e / ((size_t)ncc * 64)) * 64 + (int)(e % 64), cc = (int)(e / 64 % ncc);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int cw = cc * 4 + j;
-      uint32_t v = (o < out && cw < ncw) ? canon[((size_t)b * out + o) * ncw + cw] : 0u;
-      w[j] = rotr32(permute_word(v), b);
-    }
-  } else {
-    int rq = (int)(e / ncw), cw = (int)(e % ncw);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      int o = rq * 4 + r;
-      uint32_t v = (o < out) ? canon[((size_t)b * out + o) * ncw + cw] : 0u;
-      w[r] = rotr32(permute_word(v), b);
-    }
+  for (int j = 0; j < 4; ++j) {
+    const int cw = cc * 4 + j;
+    uint32_t v = (o < out && cw < ncw) ? canon[((size_t)b * out + o) * ncw + cw] : 0u;
+    w[j] = rotr32(permute_word(v), b);
   }
   dev[(size_t)b * plane_stride_u4 + e] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// table [out][entries] -> [nrq*4][entries], zero rows appended
+// table [out][entries] -> [rows_padded][entries], zero rows appended
 __global__ void copy_lut_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, int out,
                                 int rows_padded, int entries) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -53,13 +43,13 @@ __global__ void copy_lut_kernel(const uint16_t* __restrict__ src, uint16_t* __re
 
 // device planes -> canonical k-bit codes uint8 [out][in]; one thread per (row, column word)
 __global__ void debug_unpack_kernel(const uint32_t* __restrict__ dev, size_t plane_stride_u32, int p, int k,
-                                    int out, int ncw, int ncc, int row_lane, uint8_t* __restrict__ idx) {
+                                    int out, int ncw, int ncc, uint8_t* __restrict__ idx) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)out * ncw) return;
   int o = (int)(i / ncw), cw = (int)(i % ncw);
   uint32_t w[8];
   for (int b = 0; b < p; ++b) {
-    uint32_t s = dev[(size_t)b * plane_stride_u32 + plane_word_index(row_lane, o, cw, ncw, ncc)];
+    uint32_t s = dev[(size_t)b * plane_stride_u32 + plane_word_index(o, cw, ncc)];
     w[b] = unpermute_word((s << b) | (b ? (s >> (32 - b)) : 0u));  // undo rotation and permutation
   }
   for (int c = 0; c < 32; ++c) {
@@ -67,6 +57,13 @@ __global__ void debug_unpack_kernel(const uint32_t* __restrict__ dev, size_t pla
     for (int b = 0; b < p; ++b) code = (code << 1) | ((w[b] >> c) & 1u);
     idx[(size_t)o * ncw * 32 + (size_t)cw * 32 + c] = (uint8_t)(code >> (p - k));
   }
+}
+
+// n 32-bit words = v: clears counters and sets the target word (a kernel, not a memset node, so that a caller may
+// capture it in a graph)
+__global__ void fill_u32_kernel(uint32_t* __restrict__ dst, size_t n, uint32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = v;
 }
 
 // plain 128-bit copy of a known size: the yardstick the HBM byte counters are scaled by

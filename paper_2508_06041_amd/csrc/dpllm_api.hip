@@ -13,7 +13,6 @@
 
 #include "../../include/dpllm.h"
 #include "aux_kernels.hpp"
-#include "gemv_fast.hpp"
 #include "gemv_kernels.hpp"
 #include "gemv_lane.hpp"
 #include "layout.hpp"
@@ -23,46 +22,62 @@ using namespace dpllm;
 
 namespace {
 
-struct Selector {
+struct Pair {
   bool set = false;
   int l = 0, h = 0, kind = DPLLM_SEL_NONE, r = 0;
   const uint16_t* G = nullptr;
   float alpha = 0.f, beta = 0.f, T = 0.f;
 };
 
+struct TargetEntry {   // what a linear runs under one of the targets 1 .. DPLLM_MAX_TARGETS - 1
+  bool set = false;
+  int slot = 0;
+  float T = 0.f;
+};
+
 struct Linear {
   bool loaded = false;
   LinearLayout L;
   char* arena = nullptr;
-  Selector sel[DPLLM_MAX_PAIRS];
-  int active = -1;
-  const void* sel_input = nullptr;   // decode step: the selector reads this vector instead of the linear's input
-  const uint4* planes() const { return reinterpret_cast<const uint4*>(arena); }
-  const uint16_t* lut(int k) const { return reinterpret_cast<const uint16_t*>(arena + L.lut_offset[k]); }
+  Pair sel[DPLLM_MAX_PAIRS];
+  int active = -1;                     // the pair of target 0
+  TargetEntry tgt[DPLLM_MAX_TARGETS];  // [0] unused
+  const void* sel_input = nullptr;     // decode step: the selector reads this vector instead of the linear's input
   int find_pair(int l, int h) const {
     for (int i = 0; i < DPLLM_MAX_PAIRS; ++i)
       if (sel[i].set && sel[i].l == l && sel[i].h == h) return i;
     return -1;
   }
+  // what the launches are sized for: the properties of all pairs the linear holds, whichever is in use
+  int max_rowgroups() const {
+    int g = 0;
+    for (const Pair& s : sel)
+      if (s.set) g = std::max(g, sel_rowgroups_of(s.kind, s.r));
+    return g;
+  }
+  int part_k() const {   // the bitwidth the work of a step launch is cut for: the larger one of the pair of target 0
+    return active >= 0 ? sel[active].h : L.p;
+  }
+  bool streaming() const {   // every bitwidth its selectors can ask for has a decode scheme in the streaming kernel
+    for (const Pair& s : sel)
+      if (s.set && (s.l < kFastKMin || s.h > kFastKMax)) return false;
+    return true;
+  }
 };
 
 // A decode step is cut into phases: maximal runs of consecutive linears none of which reads or overwrites
 // what an earlier linear of the run writes.  Inside a phase all selectors run in one launch and all GEMVs
-// of one candidate pair in another; phases run one after the other on the stream, so the result equals
-// running the linears strictly in order.
-struct GemvLaunch {
-  int ka, kb;          // kernel instance; ka == kb == 0: the plain kernel, one launch per job
-  int mode;            // arrangement of the planes of the linears in this launch
-  int first, count;    // slice of the device job table
-  int blocks;          // workgroups of the launch
-  int block_first;     // slice of the device workgroup-to-job table
-};
+// in another; phases run one after the other on the stream, so the result equals running the linears strictly
+// in order.
 struct Phase {
-  int sel_first, sel_count;     // slice of the device selector job table
-  int part_first, part_count;   // slice of the device selector part table
-  std::vector<GemvLaunch> gemv;
+  int sel_first = 0, sel_count = 0;     // slice of the device selector job table
+  int part_first = 0, part_count = 0;   // slice of the device selector part table
+  int gemv_first = 0, gemv_count = 0;   // slice of the device GEMV job table (streaming kernel, one launch)
+  int blocks = 0;                       // workgroups of that launch
+  int block_first = 0;                  // slice of the device workgroup-to-job table
+  std::vector<int> plain;               // linears served by the plain kernel, one launch each
 };
-constexpr int kLanePoolRows = 8192;
+constexpr int kLanePoolRows = 8192;     // row blocks x splits of the column-split launches that may be in flight
 constexpr size_t kSelOneSlots = (size_t)kSelMaxChunks * kSelMaxRank;
 
 struct StepPlan {
@@ -73,8 +88,24 @@ struct StepPlan {
   int32_t* k_dev = nullptr;
   float* e_dev = nullptr;
   std::vector<Phase> phases;
-  std::vector<GemvJob> gemv_jobs;   // host copies (also used for plain launches)
-  std::vector<int> gemv_ids;        // linear id of every gemv job
+};
+
+// The caller's workspace, carved once by dpllm_set_workspace.  Offsets in bytes, every region 256-byte aligned.
+struct Workspace {
+  char* base = nullptr;
+  size_t bytes = 0;
+  size_t lane_ws = 0, lane_cnt = 0;          // column-split pool: kLanePoolRows x 64 fp32, kLanePoolRows counters
+  size_t est_ws = 0, est_ticket = 0;         // dpllm_estimate: kSelOneSlots fp64, one counter
+  size_t target = 0;                         // the number of the active target
+  size_t sel_params = 0;                     // SelParams [DPLLM_MAX_TARGETS][n]
+  size_t sel_jobs = 0, sel_tickets = 0;      // SelJob [n], counters [n]
+  size_t sel_parts = 0, sel_parts_cap = 0;   // SelPart [cap]
+  size_t sel_ws = 0, sel_ws_cap = 0;         // fp64 [cap]
+  size_t gemv_jobs = 0;                      // GemvJob [n]
+  size_t block_jobs = 0, block_jobs_cap = 0; // int32 [cap]
+  size_t total = 0;
+  template <class T>
+  T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
 };
 
 }  // namespace
@@ -82,24 +113,16 @@ struct StepPlan {
 struct dpllm_model {
   std::vector<Linear> linears;
   std::string err;
-  uint64_t version = 1;            // bumped by every call that changes what a plan depends on
-  int layout = kLayoutRowLane;     // arrangement given to linears loaded from now on
-  // decode-step plan and its device tables
+  uint64_t version = 1;            // bumped by every call that changes what the launch plan depends on
+  bool params_dirty = true;        // the device table of selector parameters is behind the host's
   StepPlan plan;
-  SelJob* d_sel_jobs = nullptr;
-  SelPart* d_sel_parts = nullptr;
-  size_t sel_parts_cap = 0;
-  double* d_sel_ws = nullptr;       // the workspace slots of every selector job of the plan
-  size_t sel_ws_cap = 0;
-  double* d_sel_ws_one = nullptr;   // kSelMaxChunks x kSelMaxRank slots for dpllm_estimate, then its arrival counter
-  uint32_t* d_sel_tickets = nullptr;  // one arrival counter per linear of the plan, zero between launches
-  GemvJob* d_gemv_jobs = nullptr;
-  int32_t* d_block_jobs = nullptr;   // for every workgroup of every multi-job GEMV launch of the plan: its job
-  size_t block_jobs_cap = 0;
-  // column-split launches of the row-per-lane kernel: partial sums (kLanePoolRows x 64 fp32) and arrival counters
-  // (kLanePoolRows, zero whenever no launch is running); one launch at a time uses them
-  float* d_lane_ws = nullptr;
-  uint32_t* d_lane_cnt = nullptr;
+  Workspace ws;
+  // host copies of what the plan puts into the workspace (kept so that the asynchronous copies have a source)
+  std::vector<SelJob> h_sel_jobs;
+  std::vector<SelPart> h_sel_parts;
+  std::vector<GemvJob> h_gemv_jobs;
+  std::vector<int32_t> h_block_jobs;
+  std::vector<SelParams> h_params;
   int device = 0;
 };
 
@@ -141,21 +164,64 @@ Linear* get_linear(dpllm_model* m, int id, int* rc) {
   return lin;
 }
 
+// ---- workspace ------------------------------------------------------------------------------------------------
+// Sized for any launch plan over the linears as they stand (shapes, pairs): the caps are upper bounds.
+Workspace carve_workspace(const dpllm_model* m) {
+  Workspace w;
+  const size_t n = m->linears.size();
+  size_t parts = 0, slots = 0, blocks = 0;
+  for (const Linear& lin : m->linears) {
+    if (!lin.loaded) continue;
+    const size_t rg = (size_t)std::max(1, lin.max_rowgroups());
+    parts += rg * kSelMaxChunks + 1;
+    slots += rg * kSelPartRows * kSelMaxChunks;
+    blocks += (size_t)lin.L.nrq * 8;
+  }
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kAlign); return o; };
+  w.lane_ws = take(sizeof(float) * 64 * kLanePoolRows);
+  w.lane_cnt = take(sizeof(uint32_t) * kLanePoolRows);
+  w.est_ws = take(sizeof(double) * kSelOneSlots);
+  w.est_ticket = take(sizeof(uint32_t));
+  w.target = take(sizeof(int32_t));
+  w.sel_params = take(sizeof(SelParams) * DPLLM_MAX_TARGETS * n);
+  w.sel_jobs = take(sizeof(SelJob) * n);
+  w.sel_tickets = take(sizeof(uint32_t) * n);
+  w.sel_parts_cap = parts;
+  w.sel_parts = take(sizeof(SelPart) * parts);
+  w.sel_ws_cap = slots;
+  w.sel_ws = take(sizeof(double) * slots);
+  w.gemv_jobs = take(sizeof(GemvJob) * n);
+  w.block_jobs_cap = blocks;
+  w.block_jobs = take(sizeof(int32_t) * blocks);
+  w.total = off;
+  return w;
+}
+
 // ---- selector ---------------------------------------------------------------------------------------------
+SelParams make_params(const Pair& s, float T) {
+  SelParams P;
+  P.G = s.G;
+  P.T = T; P.alpha = s.alpha; P.beta = s.beta;
+  P.r = s.r; P.l = s.l; P.h = s.h; P.kind = s.kind;
+  P.pad = 0;
+  return P;
+}
+
 // launch_rowgroups: groups of 16 rows of G over all jobs of the launch.  A launch with fewer of them than
 // would fill the chip cuts the columns into chunks (multiples of 512 columns) as well.
-SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* e_dev, int32_t* k_dev, long launch_rowgroups) {
+SelJob make_sel_job(const Linear& lin, int linear, int rowgroups, const void* x, float* e_dev, int32_t* k_dev, long launch_rowgroups) {
   SelJob j;
-  j.G = s.G;
   j.x = (const uint16_t*)x;
   j.e_out = e_dev;
   j.k_out = k_dev;
-  j.T = s.T; j.alpha = s.alpha; j.beta = s.beta;
-  j.in = lin.L.in; j.r = s.r;
-  j.l = s.l; j.h = s.h; j.kind = s.kind;
+  j.ws = nullptr;
+  j.ticket = nullptr;
+  j.in = lin.L.in;
+  j.linear = linear;
   j.nchunks = 1;
   j.chunk_cols = lin.L.in;
-  if (s.kind == 1) {
+  if (rowgroups > 0) {
     // long rows are cut as well, so that the parts of a launch are of similar size (7B step: 32.5 -> 30.7 us)
     constexpr long max_cols = 4096;
     long want = std::min<long>(kSelMaxChunks, 512 / std::max<long>(1, launch_rowgroups));
@@ -165,75 +231,23 @@ SelJob make_sel_job(const Linear& lin, const Selector& s, const void* x, float* 
       j.nchunks = (lin.L.in + j.chunk_cols - 1) / j.chunk_cols;
     }
   }
-  j.nparts = sel_rowgroups_of(s.kind, s.r) * j.nchunks;
-  j.ws = nullptr;
-  j.ticket = nullptr;
+  j.ws_rows = std::max(1, rowgroups) * kSelPartRows;
+  j.next = -1;
   return j;
 }
 
 // ---- GEMV -------------------------------------------------------------------------------------------------
-// Kernel instances: a fixed bitwidth k (k, k) and the adjacent candidate pairs (k, k + 1), k >= 3.  Anything
-// else (k < 3, non-adjacent pairs) is served by the plain kernel.  A batch of B right-hand sides runs in
-// groups of two (B = 2) or four samples inside one launch; a group decodes every weight once and multiplies it
-// with each of its samples.
-bool has_fast_kernel(int ka, int kb) { return ka >= 3 && kb <= 8 && (kb == ka || kb == ka + 1); }
-
-// Right-hand sides that share one pass over the planes.  A batch B runs as ceil(B / group) groups.
-template <int KA, int KB, int NB>
-void launch_group_t(int njobs, const GemvJob& one, hipStream_t st) {
-  const int groups = (njobs + NB - 1) / NB;
-  hipLaunchKernelGGL((gemv_kernel<KA, KB, NB>), dim3(one.nblocks * groups), dim3(64), 0, st, (const GemvJob*)nullptr,
-                     (const int32_t*)nullptr, njobs, one);
-}
-
-template <int KA, int KB>
-void launch_fast_t(const GemvJob* d_jobs, const int32_t* d_block_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
-  if (d_jobs == nullptr && njobs > 1) {
-    // measured on 8B shapes: two samples per pass are fastest for B = 2, four per pass from B = 3 on
-    if (njobs == 2) launch_group_t<KA, KB, 2>(njobs, one, st);
-    else launch_group_t<KA, KB, 4>(njobs, one, st);
-  } else {
-    hipLaunchKernelGGL((gemv_kernel<KA, KB, 1>), dim3(blocks), dim3(64), 0, st, d_jobs, d_block_jobs, njobs, one);
-  }
-}
-
-// row-per-lane arrangement: a batch runs in groups of two samples that share one pass over the planes
-template <int KA, int KB>
-void launch_lane_t(const GemvJob* d_jobs, const int32_t* d_block_jobs, int njobs, const GemvJob& one, int blocks, hipStream_t st) {
-  if (d_jobs == nullptr && njobs > 1)
-    hipLaunchKernelGGL((gemv_lane_kernel<KA, KB, 2>), dim3(one.nblocks * ((njobs + 1) / 2)), dim3(kLaneThreads), 0, st, d_jobs,
-                       d_block_jobs, njobs, one);
-  else
-    hipLaunchKernelGGL((gemv_lane_kernel<KA, KB, 1>), dim3(d_jobs == nullptr ? one.nblocks : blocks), dim3(kLaneThreads), 0, st,
-                       d_jobs, d_block_jobs, njobs, one);
-}
-
-// d_jobs != nullptr: a table of jobs, d_block_jobs[b] = index in it of the job workgroup b works for
-void launch_fast(int mode, int ka, int kb, const GemvJob* d_jobs, const int32_t* d_block_jobs, int njobs, const GemvJob& one,
-                 int blocks, hipStream_t st) {
-#define DPLLM_CASE(A, B)                                                            \
-  case (A) * 16 + (B):                                                              \
-    if (mode == kLayoutRowLane) launch_lane_t<A, B>(d_jobs, d_block_jobs, njobs, one, blocks, st); \
-    else launch_fast_t<A, B>(d_jobs, d_block_jobs, njobs, one, blocks, st);                       \
-    break;
-  switch (ka * 16 + kb) {
-    DPLLM_CASE(3, 3) DPLLM_CASE(4, 4) DPLLM_CASE(5, 5) DPLLM_CASE(6, 6) DPLLM_CASE(7, 7) DPLLM_CASE(8, 8)
-    DPLLM_CASE(3, 4) DPLLM_CASE(4, 5) DPLLM_CASE(5, 6) DPLLM_CASE(6, 7) DPLLM_CASE(7, 8)
-    default: break;
-  }
-#undef DPLLM_CASE
-}
-
-GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y) {
+GemvJob make_gemv_job(const Linear& lin, int k, const int32_t* k_dev, const void* x, void* y) {
   GemvJob j;
   j.arena = lin.arena;
   j.x = (const uint16_t*)x;
   j.y = (uint16_t*)y;
   j.k_dev = k_dev;
   j.plane_stride_u4 = (uint32_t)(lin.L.plane_bytes / 16);
-  j.lut_off_a = (uint32_t)lin.L.lut_offset[ka];
-  j.lut_off_b = (uint32_t)lin.L.lut_offset[kb];
-  j.ka = ka; j.kb = kb;
+  for (int kk = kFastKMin; kk <= kFastKMax; ++kk)
+    j.lut_off[kk - kFastKMin] = (kk >= lin.L.kmin && kk <= lin.L.p) ? (uint32_t)lin.L.lut_offset[kk] : 0u;
+  j.k = k;
+  j.kmin = lin.L.kmin; j.p = lin.L.p;
   j.out = lin.L.out; j.ncw = lin.L.ncw; j.nrq = lin.L.nrq; j.ncc = lin.L.ncc;
   j.nblocks = lin.L.nrq;
   j.block_start = 0;
@@ -244,18 +258,11 @@ GemvJob make_gemv_job(const Linear& lin, int ka, int kb, const int32_t* k_dev, c
   return j;
 }
 
-// row quads one wavefront streams (workgroup b of a job takes row quads b, b + nblocks, ...): enough
-// wavefronts to fill the chip several times over, long enough runs to amortise the pipeline fill
-int pick_rq_per_block(long total_rq) {
-  long r = total_rq / 8192;
-  return (int)std::min<long>(8, std::max<long>(1, r));
-}
-
-// Row-per-lane arrangement: blocks of 64 rows one workgroup (eight wavefronts) streams.  A workgroup should
-// run for the better part of a hundred microseconds (about 1 MiB of planes): shorter ones pay their start-up
-// (job record, tables, first loads: a few microseconds of an otherwise idle slot) too often, longer ones leave
-// the chip half empty at the end of the launch (measured on the 7B step: 0.25 MiB 496 us, 0.375 MiB 480,
-// 0.75 MiB 471, 1 MiB 468, 2 MiB 477, 4 MiB 546); and a launch wants at least a few workgroups per compute unit.
+// Blocks of 64 rows one workgroup (eight wavefronts) streams.  A workgroup should run for the better part of a
+// hundred microseconds (about 1 MiB of planes): shorter ones pay their start-up (job record, tables, first
+// loads: a few microseconds of an otherwise idle slot) too often, longer ones leave the chip half empty at the
+// end of the launch (measured on the 7B step: 0.25 MiB 496 us, 0.375 MiB 480, 0.75 MiB 471, 1 MiB 468, 2 MiB
+// 477, 4 MiB 546); and a launch wants at least a few workgroups per compute unit.
 constexpr long kLaneGroupBytes = 1048576;
 int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks, long group_bytes = kLaneGroupBytes) {
   const long bytes_per_block = 64L * L.in * k / 8;
@@ -264,10 +271,10 @@ int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks, long 
   return (int)r;
 }
 
-// Row-per-lane arrangement, launches with fewer workgroups than compute units (a workgroup is tied to 64 rows):
-// the workgroups that share a block of rows.  Measured on 4096 .. 28672 rows x 4096 .. 14336 columns: splitting
-// pays only below about one workgroup per compute unit (64 blocks of rows: 23 -> 12 us at 14336 columns) and costs
-// above it (172 blocks: 9 -> 12 us), since every split builds the tables again and runs fewer tiles per wavefront.
+// Launches with fewer workgroups than compute units (a workgroup is tied to 64 rows): the workgroups that share
+// a block of rows.  Measured on 4096 .. 28672 rows x 4096 .. 14336 columns: splitting pays only below about one
+// workgroup per compute unit (64 blocks of rows: 23 -> 12 us at 14336 columns) and costs above it (172 blocks:
+// 9 -> 12 us), since every split builds the tables again and runs fewer tiles per wavefront.
 // workgroups = those of the whole launch before splitting; rows = blocks of rows x samples per pass x groups of
 // the job; pool = what is left of the partial-sum pool.
 int pick_lane_split(const LinearLayout& L, long workgroups, long rows, long pool) {
@@ -279,22 +286,20 @@ int pick_lane_split(const LinearLayout& L, long workgroups, long rows, long pool
 
 template <int B>
 void launch_plain_t(const GemvArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(gemv_plain_kernel<B>, dim3((a.nrq + 3) / 4), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(gemv_plain_kernel<B>, dim3((a.out + 15) / 16), dim3(256), 0, st, a);
 }
 
-int launch_plain(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y,
-                 int B, hipStream_t st) {
+int launch_plain(dpllm_model* m, const Linear& lin, int k, const int32_t* k_dev, const void* x, void* y, int B, hipStream_t st) {
   GemvArgs a;
-  a.planes = (const uint32_t*)lin.arena;
-  a.plane_stride_u32 = lin.L.plane_bytes / 4;
-  a.ka = ka; a.kb = kb;
-  a.lut_a = lin.lut(ka);
-  a.lut_b = k_dev ? lin.lut(kb) : nullptr;
+  a.arena = lin.arena;
+  a.plane_bytes = lin.L.plane_bytes;
+  for (int kk = 0; kk <= 8; ++kk) a.lut_off[kk] = (kk >= lin.L.kmin && kk <= lin.L.p) ? (uint32_t)lin.L.lut_offset[kk] : 0u;
+  a.k = k;
   a.k_dev = k_dev;
+  a.kmin = lin.L.kmin; a.p = lin.L.p;
   a.x = (const uint16_t*)x;
   a.y = (uint16_t*)y;
-  a.out = lin.L.out; a.in = lin.L.in; a.ncw = lin.L.ncw; a.nrq = (lin.L.out + 3) / 4;
-  a.ncc = lin.L.ncc; a.row_lane = lin.L.mode == kLayoutRowLane;
+  a.out = lin.L.out; a.in = lin.L.in; a.ncw = lin.L.ncw; a.ncc = lin.L.ncc;
   switch (B) {
     case 1: launch_plain_t<1>(a, st); break;
     case 2: launch_plain_t<2>(a, st); break;
@@ -310,20 +315,26 @@ int launch_plain(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_
   return DPLLM_OK;
 }
 
-int launch_gemv(dpllm_model* m, const Linear& lin, int ka, int kb, const int32_t* k_dev, const void* x, void* y,
-                int B, hipStream_t st) {
-  if (!has_fast_kernel(ka, kb)) return launch_plain(m, lin, ka, kb, k_dev, x, y, B, st);
-  GemvJob j = make_gemv_job(lin, ka, kb, k_dev, x, y);
-  const int rpb = lin.L.mode == kLayoutRowLane ? pick_blocks_per_group(lin.L, kb, lin.L.nrq) : pick_rq_per_block(lin.L.nrq);
+// one linear, B right-hand sides: a batch runs in groups of two samples that share one pass over the planes
+int launch_gemv(dpllm_model* m, const Linear& lin, int k, const int32_t* k_dev, const void* x, void* y, int B, hipStream_t st) {
+  const bool streaming = k_dev ? lin.L.kmin >= kFastKMin : (k >= kFastKMin && k <= kFastKMax);
+  if (!streaming) return launch_plain(m, lin, k, k_dev, x, y, B, st);
+  GemvJob j = make_gemv_job(lin, k, k_dev, x, y);
+  const int rpb = pick_blocks_per_group(lin.L, k_dev ? lin.L.p : k, lin.L.nrq);
   j.nblocks = (lin.L.nrq + rpb - 1) / rpb;
-  if (lin.L.mode == kLayoutRowLane) {
-    const long groups = B > 1 ? (B + 1) / 2 : 1, per_pass = B > 1 ? 2 : 1;
+  const long groups = B > 1 ? (B + 1) / 2 : 1, per_pass = B > 1 ? 2 : 1;
+  if (m->ws.base) {   // without a workspace there is no pool for partial sums: no column split
     j.nsplit = pick_lane_split(lin.L, j.nblocks * groups, (long)lin.L.nrq * per_pass * groups, kLanePoolRows);
     j.nblocks *= j.nsplit;
-    j.ws = m->d_lane_ws;
-    j.cnt = m->d_lane_cnt;
+    j.ws = m->ws.at<float>(m->ws.lane_ws);
+    j.cnt = m->ws.at<uint32_t>(m->ws.lane_cnt);
   }
-  launch_fast(lin.L.mode, ka, kb, nullptr, nullptr, B, j, j.nblocks * B, st);
+  if (B > 1)
+    hipLaunchKernelGGL((gemv_lane_kernel<2>), dim3(j.nblocks * (unsigned)groups), dim3(kLaneThreads), 0, st, (const GemvJob*)nullptr,
+                       (const int32_t*)nullptr, B, j);
+  else
+    hipLaunchKernelGGL((gemv_lane_kernel<1>), dim3(j.nblocks), dim3(kLaneThreads), 0, st, (const GemvJob*)nullptr,
+                       (const int32_t*)nullptr, 1, j);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -334,9 +345,34 @@ bool overlap(const void* a, size_t an, const void* b, size_t bn) {
   return a0 < b0 + bn && b0 < a0 + an;
 }
 
-int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev, float* e_dev,
-               hipStream_t st) {
+// the table of selector parameters: row t = what every linear runs under target t (rows of targets that hold no
+// entry of their own for a linear repeat target 0)
+void fill_params(dpllm_model* m) {
+  const size_t n = m->linears.size();
+  m->h_params.assign((size_t)DPLLM_MAX_TARGETS * n, SelParams{});
+  for (size_t i = 0; i < n; ++i) {
+    const Linear& lin = m->linears[i];
+    if (!lin.loaded || lin.active < 0) continue;
+    const Pair& base = lin.sel[lin.active];
+    for (int t = 0; t < DPLLM_MAX_TARGETS; ++t) {
+      const TargetEntry& e = lin.tgt[t];
+      const bool own = t > 0 && e.set && lin.sel[e.slot].set;
+      m->h_params[(size_t)t * n + i] = own ? make_params(lin.sel[e.slot], e.T) : make_params(base, base.T);
+    }
+  }
+}
+
+int upload_params(dpllm_model* m, hipStream_t st) {
+  fill_params(m);
+  HIP_TRY(m, hipMemcpyAsync(m->ws.at<SelParams>(m->ws.sel_params), m->h_params.data(), sizeof(SelParams) * m->h_params.size(),
+                            hipMemcpyHostToDevice, st));
+  m->params_dirty = false;
+  return DPLLM_OK;
+}
+
+int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev, float* e_dev, hipStream_t st) {
   const int n = (int)m->linears.size();
+  const Workspace& W = m->ws;
   StepPlan& P = m->plan;
   P.valid = false;
   P.xs.assign(xs, xs + n);
@@ -344,18 +380,11 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   P.k_dev = k_dev;
   P.e_dev = e_dev;
   P.phases.clear();
-  P.gemv_jobs.clear();
-  P.gemv_ids.clear();
-  if (!m->d_sel_jobs) {
-    HIP_TRY(m, hipMalloc((void**)&m->d_sel_jobs, sizeof(SelJob) * n));
-    HIP_TRY(m, hipMalloc((void**)&m->d_gemv_jobs, sizeof(GemvJob) * n));
-    HIP_TRY(m, hipMalloc((void**)&m->d_sel_tickets, sizeof(uint32_t) * n));
-    HIP_TRY(m, hipMemset(m->d_sel_tickets, 0, sizeof(uint32_t) * n));
-  }
-  std::vector<SelJob> sel_jobs;
-  std::vector<SelPart> sel_parts;
-  std::vector<int32_t> block_jobs;
-  std::vector<size_t> ws_offset;
+  std::vector<SelJob>& sel_jobs = m->h_sel_jobs;
+  std::vector<SelPart>& sel_parts = m->h_sel_parts;
+  std::vector<GemvJob>& gemv_jobs = m->h_gemv_jobs;
+  std::vector<int32_t>& block_jobs = m->h_block_jobs;
+  sel_jobs.clear(); sel_parts.clear(); gemv_jobs.clear(); block_jobs.clear();
   size_t ws_slots = 0;
   // phases: maximal runs of consecutive linears that do not depend on one another
   std::vector<std::pair<int, int>> bounds;
@@ -406,146 +435,111 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     sel_of_phase[q].push_back(j);
   }
   for (size_t pi = 0; pi < bounds.size(); ++pi) {
+    long pool_used = 0;   // phases follow one another on the stream: each may use the whole partial-sum pool
     const int id = bounds[pi].first, end = bounds[pi].second;
     Phase ph;
     ph.sel_first = (int)sel_jobs.size();
     ph.sel_count = (int)sel_of_phase[pi].size();
     ph.part_first = (int)sel_parts.size();
     long launch_rowgroups = 0;
-    for (int j : sel_of_phase[pi]) {
-      const Selector& s = m->linears[j].sel[m->linears[j].active];
-      launch_rowgroups += sel_rowgroups_of(s.kind, s.r);
-    }
+    for (int j : sel_of_phase[pi]) launch_rowgroups += m->linears[j].max_rowgroups();
     for (size_t local = 0; local < sel_of_phase[pi].size(); ++local) {
       const int j = sel_of_phase[pi][local];
       const Linear& lin = m->linears[j];
-      const Selector& s = lin.sel[lin.active];
-      SelJob sj = make_sel_job(lin, s, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j, launch_rowgroups);
-      for (int part = 0; part < sj.nparts; ++part) sel_parts.push_back(SelPart{(int)local, part});
-      ws_offset.push_back(ws_slots);
-      ws_slots += (size_t)sel_slots_of(s.kind, s.r, sj.nchunks);
+      const int rowgroups = lin.max_rowgroups();
+      SelJob sj = make_sel_job(lin, j, rowgroups, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j, launch_rowgroups);
+      for (int part = 0; part < rowgroups * sj.nchunks; ++part) sel_parts.push_back(SelPart{(int)local, part});
+      sj.ws = W.at<double>(W.sel_ws) + ws_slots;
+      sj.ticket = W.at<uint32_t>(W.sel_tickets) + sel_jobs.size();
+      ws_slots += (size_t)sj.ws_rows * sj.nchunks;
       sel_jobs.push_back(sj);
     }
+    // groups of jobs that read the same vector: one more part each, which takes the decisions that need no
+    // projection (and adds up x^2 once for the group when the linear regression asks for it)
+    for (int a = 0; a < ph.sel_count; ++a) {
+      SelJob& ja = sel_jobs[ph.sel_first + a];
+      bool head = true;
+      for (int b = 0; b < a && head; ++b) head = sel_jobs[ph.sel_first + b].x != ja.x || sel_jobs[ph.sel_first + b].in != ja.in;
+      if (!head) continue;
+      int prev = a;
+      for (int b = a + 1; b < ph.sel_count; ++b) {
+        const SelJob& jb = sel_jobs[ph.sel_first + b];
+        if (jb.x == ja.x && jb.in == ja.in) { sel_jobs[ph.sel_first + prev].next = b; prev = b; }
+      }
+      sel_parts.push_back(SelPart{a, -1});
+    }
     ph.part_count = (int)sel_parts.size() - ph.part_first;
-    // GEMV jobs of the phase, grouped by kernel instance (bitwidth pair, arrangement) in order of first appearance
-    struct Cls { int ka, kb, mode; bool operator==(const Cls& o) const { return ka == o.ka && kb == o.kb && mode == o.mode; } };
-    auto cls_of = [&](int j) {
-      const Linear& lj = m->linears[j];
-      const Selector& s = lj.sel[lj.active];
-      return has_fast_kernel(s.l, s.h) ? Cls{s.l, s.h, lj.L.mode} : Cls{0, 0, 0};
-    };
-    std::vector<Cls> classes;
+    // GEMV jobs of the phase: one launch of the streaming kernel for all linears it serves
+    ph.gemv_first = (int)gemv_jobs.size();
+    ph.block_first = (int)block_jobs.size();
+    long total_rq = 0, lane_groups = 0;
+    for (int j = id; j < end; ++j)
+      if (m->linears[j].streaming()) total_rq += m->linears[j].L.nrq;
     for (int j = id; j < end; ++j) {
-      Cls c = cls_of(j);
-      if (std::find(classes.begin(), classes.end(), c) == classes.end()) classes.push_back(c);
+      const Linear& lin = m->linears[j];
+      if (!lin.streaming()) continue;
+      const int rpb = pick_blocks_per_group(lin.L, lin.part_k(), total_rq);
+      lane_groups += (lin.L.nrq + rpb - 1) / rpb;
     }
-    for (const Cls& c : classes) {
-      GemvLaunch gl;
-      gl.ka = c.ka; gl.kb = c.kb; gl.mode = c.mode;
-      gl.first = (int)P.gemv_jobs.size();
-      gl.block_first = (int)block_jobs.size();
-      long total_rq = 0;
-      for (int j = id; j < end; ++j)
-        if (cls_of(j) == c) total_rq += m->linears[j].L.nrq;
-      const int rpb_quad = pick_rq_per_block(total_rq);
-      long lane_groups = 0;   // workgroups of the launch in the row-per-lane arrangement, before any split
-      if (c.mode == kLayoutRowLane)
-        for (int j = id; j < end; ++j)
-          if (cls_of(j) == c) {
-            const LinearLayout& L = m->linears[j].L;
-            const int rpb = pick_blocks_per_group(L, c.kb, total_rq);
-            lane_groups += (L.nrq + rpb - 1) / rpb;
-          }
-      std::vector<long> bytes_after(end - id, 0);   // plane bytes of the launch that follow linear j
-      {
-        long acc = 0;
-        for (int j = end - 1; j >= id; --j) {
-          if (!(cls_of(j) == c)) continue;
-          bytes_after[j - id] = acc;
-          const LinearLayout& L = m->linears[j].L;
-          acc += (long)L.nrq * 64 * L.in * (c.ka + c.kb) / 16;
-        }
-      }
-      // Large launches: the linears dispatched last (one round of workgroups: two on each of 256 compute units)
-      // get workgroups of half the usual work, so that the chip drains in less time at the end of the launch
-      // (measured on the 7B step: 0.5 - 0.8 % of the launch; quarters and eighths did not add to that).
-      const bool taper = c.mode == kLayoutRowLane && lane_groups >= 2048;
-      long pool_used = 0;
-      int blocks = 0;
-      for (int j = id; j < end; ++j) {
-        if (!(cls_of(j) == c)) continue;
+    std::vector<long> bytes_after(end - id, 0);   // plane bytes of the launch that follow linear j
+    {
+      long acc = 0;
+      for (int j = end - 1; j >= id; --j) {
         const Linear& lin = m->linears[j];
-        const Selector& s = lin.sel[lin.active];
-        GemvJob gj = make_gemv_job(lin, s.l, s.h, s.l == s.h ? nullptr : k_dev + j, xs[j], ys[j]);
-        long group_bytes = kLaneGroupBytes;
-        if (taper && bytes_after[j - id] < 512 * kLaneGroupBytes) group_bytes /= 2;
-        const int rpb = c.mode == kLayoutRowLane ? pick_blocks_per_group(lin.L, s.h, total_rq, group_bytes) : rpb_quad;
-        gj.nblocks = (lin.L.nrq + rpb - 1) / rpb;
-        if (c.mode == kLayoutRowLane) {
-          gj.nsplit = pick_lane_split(lin.L, lane_groups, lin.L.nrq, kLanePoolRows - pool_used);
-          gj.nblocks *= gj.nsplit;
-          gj.ws = m->d_lane_ws + pool_used * 64;
-          gj.cnt = m->d_lane_cnt + pool_used;
-          pool_used += (long)lin.L.nrq * gj.nsplit;
-        }
-        gj.block_start = blocks;
-        blocks += gj.nblocks;
-        block_jobs.insert(block_jobs.end(), gj.nblocks, (int32_t)(P.gemv_jobs.size() - gl.first));
-        P.gemv_jobs.push_back(gj);
-        P.gemv_ids.push_back(j);
+        if (!lin.streaming()) continue;
+        bytes_after[j - id] = acc;
+        acc += (long)lin.L.nrq * 64 * lin.L.in * lin.part_k() / 8;
       }
-      gl.count = (int)P.gemv_jobs.size() - gl.first;
-      gl.blocks = blocks;
-      ph.gemv.push_back(gl);
     }
+    // Large launches: the linears dispatched last (one round of workgroups: two on each of 256 compute units)
+    // get workgroups of half the usual work, so that the chip drains in less time at the end of the launch
+    // (measured on the 7B step: 0.5 - 0.8 % of the launch; quarters and eighths did not add to that).
+    const bool taper = lane_groups >= 2048;
+    int blocks = 0;
+    for (int j = id; j < end; ++j) {
+      const Linear& lin = m->linears[j];
+      if (!lin.streaming()) { ph.plain.push_back(j); continue; }
+      GemvJob gj = make_gemv_job(lin, 0, k_dev + j, xs[j], ys[j]);
+      long group_bytes = kLaneGroupBytes;
+      if (taper && bytes_after[j - id] < 512 * kLaneGroupBytes) group_bytes /= 2;
+      const int rpb = pick_blocks_per_group(lin.L, lin.part_k(), total_rq, group_bytes);
+      gj.nblocks = (lin.L.nrq + rpb - 1) / rpb;
+      gj.nsplit = pick_lane_split(lin.L, lane_groups, lin.L.nrq, kLanePoolRows - pool_used);
+      if (gj.nsplit > 1) {
+        gj.nblocks *= gj.nsplit;
+        gj.ws = W.at<float>(W.lane_ws) + pool_used * 64;
+        gj.cnt = W.at<uint32_t>(W.lane_cnt) + pool_used;
+        pool_used += (long)lin.L.nrq * gj.nsplit;
+      }
+      gj.block_start = blocks;
+      blocks += gj.nblocks;
+      block_jobs.insert(block_jobs.end(), gj.nblocks, (int32_t)(gemv_jobs.size() - ph.gemv_first));
+      gemv_jobs.push_back(gj);
+    }
+    ph.gemv_count = (int)gemv_jobs.size() - ph.gemv_first;
+    ph.blocks = blocks;
     P.phases.push_back(ph);
   }
-  // The tables may still be read by a step enqueued earlier: drain the stream before replacing them.
-  HIP_TRY(m, hipStreamSynchronize(st));
-  if (sel_parts.size() > m->sel_parts_cap) {
-    if (m->d_sel_parts) (void)hipFree(m->d_sel_parts);
-    m->d_sel_parts = nullptr; m->sel_parts_cap = 0;
-    HIP_TRY(m, hipMalloc((void**)&m->d_sel_parts, sizeof(SelPart) * sel_parts.size()));
-    m->sel_parts_cap = sel_parts.size();
-  }
-  if (block_jobs.size() > m->block_jobs_cap) {
-    if (m->d_block_jobs) (void)hipFree(m->d_block_jobs);
-    m->d_block_jobs = nullptr; m->block_jobs_cap = 0;
-    HIP_TRY(m, hipMalloc((void**)&m->d_block_jobs, sizeof(int32_t) * block_jobs.size()));
-    m->block_jobs_cap = block_jobs.size();
-  }
-  if (!block_jobs.empty())
-    HIP_TRY(m, hipMemcpy(m->d_block_jobs, block_jobs.data(), sizeof(int32_t) * block_jobs.size(), hipMemcpyHostToDevice));
-  if (ws_slots > m->sel_ws_cap) {
-    if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
-    m->d_sel_ws = nullptr; m->sel_ws_cap = 0;
-    HIP_TRY(m, hipMalloc((void**)&m->d_sel_ws, sizeof(double) * ws_slots));
-    m->sel_ws_cap = ws_slots;
-  }
-  for (size_t i = 0; i < sel_jobs.size(); ++i) {
-    sel_jobs[i].ws = m->d_sel_ws + ws_offset[i];
-    sel_jobs[i].ticket = m->d_sel_tickets + i;
-  }
+  if (sel_parts.size() > W.sel_parts_cap || ws_slots > W.sel_ws_cap || block_jobs.size() > W.block_jobs_cap)
+    return fail(m, DPLLM_ESTATE, "workspace too small for this step (set after the model changed?): call dpllm_workspace_bytes and "
+                                 "dpllm_set_workspace again");
+  // The tables may still be read by a step enqueued earlier on this stream: the copies are ordered behind it.
   if (!sel_parts.empty())
-    HIP_TRY(m, hipMemcpy(m->d_sel_parts, sel_parts.data(), sizeof(SelPart) * sel_parts.size(), hipMemcpyHostToDevice));
-  HIP_TRY(m, hipMemcpy(m->d_sel_jobs, sel_jobs.data(), sizeof(SelJob) * sel_jobs.size(), hipMemcpyHostToDevice));
-  HIP_TRY(m, hipMemcpy(m->d_gemv_jobs, P.gemv_jobs.data(), sizeof(GemvJob) * P.gemv_jobs.size(),
-                       hipMemcpyHostToDevice));
+    HIP_TRY(m, hipMemcpyAsync(W.at<SelPart>(W.sel_parts), sel_parts.data(), sizeof(SelPart) * sel_parts.size(), hipMemcpyHostToDevice, st));
+  if (!block_jobs.empty())
+    HIP_TRY(m, hipMemcpyAsync(W.at<int32_t>(W.block_jobs), block_jobs.data(), sizeof(int32_t) * block_jobs.size(), hipMemcpyHostToDevice, st));
+  HIP_TRY(m, hipMemcpyAsync(W.at<SelJob>(W.sel_jobs), sel_jobs.data(), sizeof(SelJob) * sel_jobs.size(), hipMemcpyHostToDevice, st));
+  if (!gemv_jobs.empty())
+    HIP_TRY(m, hipMemcpyAsync(W.at<GemvJob>(W.gemv_jobs), gemv_jobs.data(), sizeof(GemvJob) * gemv_jobs.size(), hipMemcpyHostToDevice, st));
   P.version = m->version;
   P.valid = true;
   return DPLLM_OK;
 }
 
-void free_device(dpllm_model* m) {
-  if (m->d_sel_jobs) (void)hipFree(m->d_sel_jobs);
-  if (m->d_sel_parts) (void)hipFree(m->d_sel_parts);
-  if (m->d_sel_ws) (void)hipFree(m->d_sel_ws);
-  if (m->d_sel_ws_one) (void)hipFree(m->d_sel_ws_one);
-  if (m->d_sel_tickets) (void)hipFree(m->d_sel_tickets);
-  if (m->d_gemv_jobs) (void)hipFree(m->d_gemv_jobs);
-  if (m->d_block_jobs) (void)hipFree(m->d_block_jobs);
-  if (m->d_lane_ws) (void)hipFree(m->d_lane_ws);
-  if (m->d_lane_cnt) (void)hipFree(m->d_lane_cnt);
+bool capturing(hipStream_t st) {
+  hipStreamCaptureStatus s = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &s) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return s != hipStreamCaptureStatusNone;
 }
 
 }  // namespace
@@ -560,16 +554,6 @@ int dpllm_model_create(dpllm_model** out, int n_linears) {
   m->linears.resize(n_linears);
   if (hipGetDevice(&m->device) != hipSuccess) {
     (void)hipGetLastError();
-    free_device(m);
-    delete m;
-    return DPLLM_EHIP;
-  }
-  if (hipMalloc((void**)&m->d_lane_ws, sizeof(float) * 64 * kLanePoolRows) != hipSuccess ||
-      hipMalloc((void**)&m->d_lane_cnt, sizeof(uint32_t) * kLanePoolRows) != hipSuccess ||
-      hipMemset(m->d_lane_cnt, 0, sizeof(uint32_t) * kLanePoolRows) != hipSuccess ||
-      hipDeviceSynchronize() != hipSuccess) {
-    (void)hipGetLastError();
-    free_device(m);
     delete m;
     return DPLLM_EHIP;
   }
@@ -577,11 +561,7 @@ int dpllm_model_create(dpllm_model** out, int n_linears) {
   return DPLLM_OK;
 }
 
-void dpllm_model_destroy(dpllm_model* m) {
-  if (!m) return;
-  free_device(m);
-  delete m;
-}
+void dpllm_model_destroy(dpllm_model* m) { delete m; }
 
 const char* dpllm_last_error(const dpllm_model* m) { return m ? m->err.c_str() : "null model"; }
 
@@ -589,9 +569,34 @@ int dpllm_linear_device_bytes(int out, int in, int p, int kmin, size_t* bytes) {
   if (!bytes) return DPLLM_EINVAL;
   int rc = check_shape(out, in, p, kmin);
   if (rc != DPLLM_OK) return rc;
-  // enough for either arrangement of the planes
-  *bytes = std::max(LinearLayout::make(out, in, p, kmin, kLayoutRowQuad).total_bytes,
-                    LinearLayout::make(out, in, p, kmin, kLayoutRowLane).total_bytes);
+  *bytes = LinearLayout::make(out, in, p, kmin).total_bytes;
+  return DPLLM_OK;
+}
+
+int dpllm_workspace_bytes(const dpllm_model* m, size_t* bytes) {
+  if (!m || !bytes) return DPLLM_EINVAL;
+  *bytes = carve_workspace(m).total;
+  return DPLLM_OK;
+}
+
+int dpllm_set_workspace(dpllm_model* m, void* ws_dev, size_t bytes, void* stream) {
+  if (!m) return DPLLM_EINVAL;
+  if (!ws_dev) return fail(m, DPLLM_EINVAL, "null workspace");
+  if ((uintptr_t)ws_dev % kAlign) return fail(m, DPLLM_EINVAL, "workspace not %zu-byte aligned", kAlign);
+  Workspace w = carve_workspace(m);
+  if (bytes < w.total) return fail(m, DPLLM_ESTATE, "workspace holds %zu bytes, %zu needed", bytes, w.total);
+  w.base = (char*)ws_dev;
+  w.bytes = bytes;
+  hipStream_t st = (hipStream_t)stream;
+  // counters and the target word start at zero; everything else is written before it is read
+  const size_t n = m->linears.size();
+  struct { size_t off, words; } zero[] = {{w.lane_cnt, (size_t)kLanePoolRows}, {w.est_ticket, 1}, {w.target, 1}, {w.sel_tickets, n}};
+  for (const auto& z : zero)
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((z.words + 255) / 256)), dim3(256), 0, st, w.at<uint32_t>(z.off), z.words, 0u);
+  HIP_TRY(m, hipGetLastError());
+  m->ws = w;
+  m->params_dirty = true;
+  m->version++;
   return DPLLM_OK;
 }
 
@@ -607,7 +612,7 @@ int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin, 
   for (int k = kmin; k <= p; ++k)
     if (!luts[k - kmin]) return fail(m, DPLLM_EINVAL, "null table for k=%d", k);
   if ((uintptr_t)dev_arena % kAlign) return fail(m, DPLLM_EINVAL, "arena not %zu-byte aligned", kAlign);
-  LinearLayout L = LinearLayout::make(out, in, p, kmin, m->layout);
+  LinearLayout L = LinearLayout::make(out, in, p, kmin);
   if (arena_bytes < L.total_bytes)
     return fail(m, DPLLM_ESTATE, "arena holds %zu bytes, %zu needed", arena_bytes, L.total_bytes);
   hipStream_t st = (hipStream_t)stream;
@@ -617,7 +622,7 @@ int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin, 
   for (int k = kmin; k <= p; ++k) lut_elems_total += (size_t)out << k;
   const uint32_t* d_planes = planes;
   void* staging = nullptr;
-  if (!src_on_device) {
+  if (!src_on_device) {   // host sources pass through a device staging buffer that lives for the length of this call
     HIP_TRY(m, hipMalloc(&staging, plane_words * 4 + lut_elems_total * 2));
     hipError_t e = hipMemcpyAsync(staging, planes, plane_words * 4, hipMemcpyHostToDevice, st);
     char* dst = (char*)staging + plane_words * 4;
@@ -630,10 +635,9 @@ int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin, 
     d_planes = (const uint32_t*)staging;
   }
   {
-    const int row_lane = L.mode == kLayoutRowLane;
-    size_t n = (row_lane ? (size_t)L.nrq * L.ncc * 64 : (size_t)L.nrq * L.ncw) * p;
+    size_t n = (size_t)L.nrq * L.ncc * 64 * p;
     hipLaunchKernelGGL(retile_planes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_planes,
-                       (uint4*)dev_arena, p, out, L.ncw, L.ncc, L.nrq, row_lane, L.plane_bytes / 16);
+                       (uint4*)dev_arena, p, out, L.ncw, L.ncc, L.nrq, L.plane_bytes / 16);
   }
   const char* lsrc = staging ? (const char*)staging + plane_words * 4 : nullptr;
   for (int k = kmin; k <= p; ++k) {
@@ -653,6 +657,7 @@ int dpllm_load_linear(dpllm_model* m, int id, int out, int in, int p, int kmin, 
   lin.L = L;
   lin.arena = (char*)dev_arena;
   m->version++;
+  m->params_dirty = true;
   return DPLLM_OK;
 }
 
@@ -679,11 +684,15 @@ int dpllm_set_selector(dpllm_model* m, int id, int l, int h, int kind, const voi
     for (int i = 0; i < DPLLM_MAX_PAIRS && slot < 0; ++i)
       if (!lin->sel[i].set) slot = i;
   if (slot < 0) return fail(m, DPLLM_ESTATE, "linear %d already holds %d pairs", id, DPLLM_MAX_PAIRS);
-  Selector& s = lin->sel[slot];
-  s.set = true; s.l = l; s.h = h; s.kind = kind; s.r = r; s.G = (const uint16_t*)G_dev;
+  Pair& s = lin->sel[slot];
+  // the launch plan is sized by the ranks and bitwidths of all pairs of the linear: it survives a change of G,
+  // alpha, beta or T
+  const bool same_shape = s.set && lin->active == slot && s.kind == kind && sel_rowgroups_of(s.kind, s.r) == sel_rowgroups_of(kind, r);
+  s.set = true; s.l = l; s.h = h; s.kind = kind; s.r = kind == DPLLM_SEL_PROJ ? r : 0; s.G = (const uint16_t*)G_dev;
   s.alpha = alpha; s.beta = beta; s.T = T;
   lin->active = slot;
-  m->version++;
+  if (!same_shape) m->version++;
+  m->params_dirty = true;
   return DPLLM_OK;
 }
 
@@ -695,7 +704,7 @@ int dpllm_set_threshold(dpllm_model* m, int id, int l, int h, float T) {
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
   lin->sel[slot].T = T;
-  m->version++;
+  m->params_dirty = true;
   return DPLLM_OK;
 }
 
@@ -705,15 +714,34 @@ int dpllm_set_active_pair(dpllm_model* m, int id, int l, int h) {
   if (!lin) return rc;
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
+  if (lin->active < 0 || lin->sel[lin->active].h != lin->sel[slot].h) m->version++;   // the step's work is cut for h
   lin->active = slot;
-  m->version++;
+  m->params_dirty = true;
   return DPLLM_OK;
 }
 
-int dpllm_model_set_layout(dpllm_model* m, int layout) {
+int dpllm_set_target_entry(dpllm_model* m, int target, int id, int l, int h, float T) {
+  int rc = DPLLM_OK;
+  Linear* lin = get_linear(m, id, &rc);
+  if (!lin) return rc;
+  if (target < 1 || target >= DPLLM_MAX_TARGETS) return fail(m, DPLLM_EINVAL, "target %d outside [1,%d]", target, DPLLM_MAX_TARGETS - 1);
+  if (std::isnan(T)) return fail(m, DPLLM_EINVAL, "threshold is NaN");
+  int slot = lin->find_pair(l, h);
+  if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
+  lin->tgt[target].set = true;
+  lin->tgt[target].slot = slot;
+  lin->tgt[target].T = T;
+  m->params_dirty = true;
+  return DPLLM_OK;
+}
+
+int dpllm_set_target(dpllm_model* m, int target, void* stream) {
   if (!m) return DPLLM_EINVAL;
-  if (layout != DPLLM_LAYOUT_ROWQUAD && layout != DPLLM_LAYOUT_ROWLANE) return fail(m, DPLLM_EINVAL, "unknown layout %d", layout);
-  m->layout = layout == DPLLM_LAYOUT_ROWLANE ? kLayoutRowLane : kLayoutRowQuad;
+  if (target < 0 || target >= DPLLM_MAX_TARGETS) return fail(m, DPLLM_EINVAL, "target %d outside [0,%d]", target, DPLLM_MAX_TARGETS - 1);
+  if (!m->ws.base) return fail(m, DPLLM_ESTATE, "no workspace set");
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, m->ws.at<uint32_t>(m->ws.target), (size_t)1,
+                     (uint32_t)target);
+  HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
 
@@ -736,17 +764,15 @@ int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, floa
   if ((uintptr_t)x_dev % 16) return fail(m, DPLLM_EINVAL, "x not 16-byte aligned");
   int slot = lin->find_pair(l, h);
   if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
-  const Selector& sel = lin->sel[slot];
-  SelJob j = make_sel_job(*lin, sel, x_dev, e_dev, k_dev, sel_rowgroups_of(sel.kind, sel.r));
-  if (!m->d_sel_ws_one) {
-    HIP_TRY(m, hipMalloc((void**)&m->d_sel_ws_one, sizeof(double) * (kSelOneSlots + 1)));
-    HIP_TRY(m, hipMemset(m->d_sel_ws_one + kSelOneSlots, 0, sizeof(double)));
-    HIP_TRY(m, hipDeviceSynchronize());
-  }
-  j.ws = m->d_sel_ws_one;
-  j.ticket = reinterpret_cast<uint32_t*>(m->d_sel_ws_one + kSelOneSlots);
-  hipLaunchKernelGGL(selector_part_kernel, dim3(j.nparts), dim3(kSelPartThreads), 0, (hipStream_t)stream,
-                     (const SelJob*)nullptr, (const SelPart*)nullptr, j);
+  if (!m->ws.base) return fail(m, DPLLM_ESTATE, "no workspace set");
+  const Pair& sel = lin->sel[slot];
+  const int rowgroups = sel_rowgroups_of(sel.kind, sel.r);
+  SelJob j = make_sel_job(*lin, id, rowgroups, x_dev, e_dev, k_dev, rowgroups);
+  j.ws = m->ws.at<double>(m->ws.est_ws);
+  j.ticket = m->ws.at<uint32_t>(m->ws.est_ticket);
+  const int blocks = sel.kind == DPLLM_SEL_PROJ ? rowgroups * j.nchunks : 1;
+  hipLaunchKernelGGL(selector_part_kernel, dim3(blocks), dim3(kSelPartThreads), 0, (hipStream_t)stream, (const SelJob*)nullptr,
+                     (const SelPart*)nullptr, (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, make_params(sel, sel.T));
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -759,14 +785,13 @@ int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* 
   if (!x_dev || !y_dev) return fail(m, DPLLM_EINVAL, "null pointer");
   if ((uintptr_t)x_dev % 16) return fail(m, DPLLM_EINVAL, "x not 16-byte aligned");
   if (B < 1 || B > DPLLM_MAX_BATCH) return fail(m, DPLLM_ESHAPE, "batch %d outside [1,%d]", B, DPLLM_MAX_BATCH);
+  if (overlap(x_dev, (size_t)B * lin->L.in * 2, y_dev, (size_t)B * lin->L.out * 2)) return fail(m, DPLLM_EINVAL, "x and y overlap");
   if (k >= 0) {
     if (k < lin->L.kmin || k > lin->L.p) return fail(m, DPLLM_ERANGE, "k=%d outside [%d,%d]", k, lin->L.kmin, lin->L.p);
-    return launch_gemv(m, *lin, k, k, nullptr, x_dev, y_dev, B, (hipStream_t)stream);
+    return launch_gemv(m, *lin, k, nullptr, x_dev, y_dev, B, (hipStream_t)stream);
   }
   if (!k_dev) return fail(m, DPLLM_EINVAL, "k < 0 needs k_dev");
-  if (lin->active < 0) return fail(m, DPLLM_ESTATE, "linear %d has no active pair", id);
-  const Selector& s = lin->sel[lin->active];
-  return launch_gemv(m, *lin, s.l, s.h, s.l == s.h ? nullptr : k_dev, x_dev, y_dev, B, (hipStream_t)stream);
+  return launch_gemv(m, *lin, 0, k_dev, x_dev, y_dev, B, (hipStream_t)stream);
 }
 
 int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev, float* e_dev,
@@ -774,10 +799,14 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
   if (!m) return DPLLM_EINVAL;
   if (parts < 1 || parts > (DPLLM_STEP_SELECT | DPLLM_STEP_GEMV)) return fail(m, DPLLM_EINVAL, "bad parts %d", parts);
   if (!xs || !ys || !k_dev || !e_dev) return fail(m, DPLLM_EINVAL, "null pointer");
+  if (!m->ws.base) return fail(m, DPLLM_ESTATE, "no workspace set");
   const int n = (int)m->linears.size();
+  hipStream_t st = (hipStream_t)stream;
   StepPlan& P = m->plan;
   bool reuse = P.valid && P.version == m->version && P.k_dev == k_dev && P.e_dev == e_dev &&
                std::equal(xs, xs + n, P.xs.begin()) && std::equal(ys, ys + n, P.ys.begin());
+  if ((!reuse || m->params_dirty) && capturing(st))
+    return fail(m, DPLLM_ESTATE, "the model changed since its last step: run one step outside stream capture first");
   if (!reuse) {
     for (int id = 0; id < n; ++id) {
       const Linear& lin = m->linears[id];
@@ -785,32 +814,32 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
       if (lin.active < 0) return fail(m, DPLLM_ESTATE, "linear %d has no selector", id);
       if (!xs[id] || !ys[id]) return fail(m, DPLLM_EINVAL, "null x or y for linear %d", id);
       if ((uintptr_t)xs[id] % 16) return fail(m, DPLLM_EINVAL, "x of linear %d not 16-byte aligned", id);
+      if (overlap(xs[id], (size_t)lin.L.in * 2, ys[id], (size_t)lin.L.out * 2)) return fail(m, DPLLM_EINVAL, "x and y of linear %d overlap", id);
     }
-    int rc = build_plan(m, xs, ys, k_dev, e_dev, (hipStream_t)stream);
+    int rc = build_plan(m, xs, ys, k_dev, e_dev, st);
     if (rc != DPLLM_OK) return rc;
   }
-  hipStream_t st = (hipStream_t)stream;
+  if (m->params_dirty) {
+    int rc = upload_params(m, st);
+    if (rc != DPLLM_OK) return rc;
+  }
+  const Workspace& W = m->ws;
   SelJob none{};
+  SelParams pnone{};
   GemvJob gnone{};
   for (const Phase& ph : P.phases) {
-    if (parts & DPLLM_STEP_SELECT) {
-      const SelJob* jobs = m->d_sel_jobs + ph.sel_first;
-      if (ph.part_count > 0)
-        hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
-                           (const SelPart*)(m->d_sel_parts + ph.part_first), none);
-    }
+    if ((parts & DPLLM_STEP_SELECT) && ph.part_count > 0)
+      hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st,
+                         (const SelJob*)(W.at<SelJob>(W.sel_jobs) + ph.sel_first), (const SelPart*)(W.at<SelPart>(W.sel_parts) + ph.part_first),
+                         (const SelParams*)W.at<SelParams>(W.sel_params), (const int32_t*)W.at<int32_t>(W.target), n, none, pnone);
     if (!(parts & DPLLM_STEP_GEMV)) continue;
-    for (const GemvLaunch& gl : ph.gemv) {
-      if (gl.ka != 0) {
-        launch_fast(gl.mode, gl.ka, gl.kb, m->d_gemv_jobs + gl.first, m->d_block_jobs + gl.block_first, gl.count, gnone,
-                    gl.blocks, st);
-      } else {
-        for (int i = gl.first; i < gl.first + gl.count; ++i) {
-          const GemvJob& j = P.gemv_jobs[i];
-          int rc = launch_plain(m, m->linears[P.gemv_ids[i]], j.ka, j.kb, j.k_dev, j.x, j.y, 1, st);
-          if (rc != DPLLM_OK) return rc;
-        }
-      }
+    if (ph.gemv_count > 0)
+      hipLaunchKernelGGL((gemv_lane_kernel<1>), dim3(ph.blocks), dim3(kLaneThreads), 0, st,
+                         (const GemvJob*)(W.at<GemvJob>(W.gemv_jobs) + ph.gemv_first), (const int32_t*)(W.at<int32_t>(W.block_jobs) + ph.block_first),
+                         ph.gemv_count, gnone);
+    for (int j : ph.plain) {
+      int rc = launch_plain(m, m->linears[j], 0, k_dev + j, xs[j], ys[j], 1, st);
+      if (rc != DPLLM_OK) return rc;
     }
   }
   HIP_TRY(m, hipGetLastError());
@@ -830,8 +859,7 @@ int dpllm_debug_unpack(dpllm_model* m, int id, int k, uint8_t* idx_dev, void* st
   if (k < 1 || k > lin->L.p) return fail(m, DPLLM_ERANGE, "k=%d outside [1,%d]", k, lin->L.p);
   size_t n = (size_t)lin->L.out * lin->L.ncw;
   hipLaunchKernelGGL(debug_unpack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                     (const uint32_t*)lin->arena, lin->L.plane_bytes / 4, lin->L.p, k, lin->L.out, lin->L.ncw, lin->L.ncc,
-                     (int)(lin->L.mode == kLayoutRowLane), idx_dev);
+                     (const uint32_t*)lin->arena, lin->L.plane_bytes / 4, lin->L.p, k, lin->L.out, lin->L.ncw, lin->L.ncc, idx_dev);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }

@@ -1,6 +1,8 @@
-// Any-precision GEMV kernels: y = W_k x with W_k[o][c] = LUT_k[o][code_p(o,c) >> (p - k)], reading
+// Plain any-precision GEMV kernel: y = W_k x with W_k[o][c] = LUT_k[o][code_p(o,c) >> (p - k)], reading
 // the top k bitplanes only (paper Sec. 3: the linear operation of a decode step is a GEMV;
-// Sec. 2.2: the k-bit model is overlaid in the parent's memory).
+// Sec. 2.2: the k-bit model is overlaid in the parent's memory).  One wavefront per four rows, one code bit
+// at a time: it serves every bitwidth from 1 to 8 and every batch, and is what runs for the bitwidths below 3,
+// which the streaming kernel (gemv_lane.hpp) has no decode scheme for.
 #pragma once
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
@@ -12,30 +14,26 @@
 namespace dpllm {
 
 struct GemvArgs {
-  const uint32_t* planes;    // device planes, plane b at planes + b * plane_stride_u32
-  size_t plane_stride_u32;
-  const uint16_t* lut_a;     // table of bitwidth ka, [nrq*4][2^ka]
-  const uint16_t* lut_b;     // table of bitwidth kb (dynamic selection) or nullptr
-  int ka, kb;
-  const int32_t* k_dev;      // nullptr: use ka; else *k_dev in {ka, kb}
+  const char* arena;         // device planes start here, plane b at + b * plane_bytes
+  size_t plane_bytes;
+  uint32_t lut_off[9];       // byte offset of the k-bit table inside the arena ([rows padded][2^k] fp16), k = kmin..p
+  int k;                     // the bitwidth when k_dev == nullptr
+  const int32_t* k_dev;      // else the bitwidth is *k_dev; a value outside [kmin, p] is not served
+  int kmin, p;
   const uint16_t* x;         // fp16 [B][in]
   uint16_t* y;               // fp16 [B][out]
-  int out, in, ncw, nrq;     // nrq: row quads (ceil(out / 4)) whatever the arrangement
-  int ncc, row_lane;         // arrangement of the words inside a plane (see layout_device.hpp)
+  int out, in, ncw, ncc;
 };
 
-// Plain kernel: one wave per row quad, one code bit at a time.  Serves every (k, B).
 template <int B>
 __global__ void __launch_bounds__(256) gemv_plain_kernel(GemvArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int rq = blockIdx.x * 4 + wave;
-  if (rq >= a.nrq) return;
-  int k = a.ka;
-  const uint16_t* lut = a.lut_a;
-  if (a.k_dev != nullptr) {
-    int kd = *a.k_dev;
-    if (kd == a.kb) { k = a.kb; lut = a.lut_b; }
-  }
+  if (rq * 4 >= a.out) return;
+  int k = a.k;
+  if (a.k_dev != nullptr) k = *a.k_dev;
+  if (k < a.kmin || k > a.p) return;
+  const uint16_t* lut = reinterpret_cast<const uint16_t*>(a.arena + a.lut_off[k]);
   float acc[4][B];
 #pragma unroll
   for (int r = 0; r < 4; ++r)
@@ -44,11 +42,12 @@ __global__ void __launch_bounds__(256) gemv_plain_kernel(GemvArgs a) {
   for (int cw = lane; cw < a.ncw; cw += 64) {
     uint4 w[8];
     for (int b = 0; b < k; ++b) {
-      const uint32_t* pl = a.planes + (size_t)b * a.plane_stride_u32;
-      w[b].x = pl[plane_word_index(a.row_lane, rq * 4 + 0, cw, a.ncw, a.ncc)];
-      w[b].y = pl[plane_word_index(a.row_lane, rq * 4 + 1, cw, a.ncw, a.ncc)];
-      w[b].z = pl[plane_word_index(a.row_lane, rq * 4 + 2, cw, a.ncw, a.ncc)];
-      w[b].w = pl[plane_word_index(a.row_lane, rq * 4 + 3, cw, a.ncw, a.ncc)];
+      const uint32_t* pl = reinterpret_cast<const uint32_t*>(a.arena + (size_t)b * a.plane_bytes);
+      // rows past `out` inside the last block of 64 are zero words of the padded layout
+      w[b].x = pl[plane_word_index(rq * 4 + 0, cw, a.ncc)];
+      w[b].y = pl[plane_word_index(rq * 4 + 1, cw, a.ncc)];
+      w[b].z = pl[plane_word_index(rq * 4 + 2, cw, a.ncc)];
+      w[b].w = pl[plane_word_index(rq * 4 + 3, cw, a.ncc)];
     }
     for (int q = 0; q < 32; ++q) {
       uint32_t code[4] = {0, 0, 0, 0};

@@ -21,12 +21,16 @@
 //   k = 3, 4 : two weights per lookup, tables of 64 / 256 fp16 pairs per row (16 / 64 KiB per workgroup)
 //   k >= 5   : one weight per lookup (table of 2^k entries per row, 8 .. 64 KiB), two results packed for one
 //              v_dot2_f32_f16
+// One kernel serves every bitwidth from 3 to 8: a workgroup reads the bitwidth of its job (a value, or the word a
+// selector wrote in device memory) and branches to the code of that bitwidth.  Every branch stays below 128 vector
+// registers and the workgroup's LDS is sized for the largest tables (64 KiB), so two workgroups share a compute
+// unit whatever the bitwidth; which bitwidth runs is never a matter for the host.
 #pragma once
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 
-#include "gemv_fast.hpp"
+#include "gemv_common.hpp"
 #include "layout_device.hpp"
 
 namespace dpllm {
@@ -50,19 +54,19 @@ struct LaneDecode {
 constexpr int kLaneRedBytes = kLaneWaves * 64 * 4;            // the partial sums of the eight wavefronts
 constexpr int kLaneKeepTiles = 4;                             // a wavefront with so few tiles per row block keeps their activations in LDS
 constexpr int kLaneXBytes = 512 + kLaneKeepTiles * 256;       // per wavefront: a tile's activations (natural, ready), kept tiles
-template <int KA, int KB>
-__host__ __device__ constexpr int lane_table_bytes() {
-  constexpr int a = LaneDecode<KA>::table_bytes, b = LaneDecode<KB>::table_bytes;
-  return a > b ? a : b;
-}
+constexpr int kLaneTableBytes = 65536;                        // the largest tables: k = 4 (pairs) and k = 8
+static_assert(LaneDecode<3>::table_bytes <= kLaneTableBytes && LaneDecode<4>::table_bytes <= kLaneTableBytes &&
+              LaneDecode<5>::table_bytes <= kLaneTableBytes && LaneDecode<6>::table_bytes <= kLaneTableBytes &&
+              LaneDecode<7>::table_bytes <= kLaneTableBytes && LaneDecode<8>::table_bytes <= kLaneTableBytes, "tables fit");
 // NB right-hand sides per pass (1 or 2): NB sets of partial sums; with two, every sample has a 512-byte slot per
 // wavefront and nothing is kept across row blocks
 template <int NB>
 __host__ __device__ constexpr int lane_x_bytes() { return NB == 1 ? kLaneXBytes : NB * 512; }
-template <int KA, int KB, int NB>
-__host__ __device__ constexpr int lane_lds_bytes() {
-  return lane_table_bytes<KA, KB>() + NB * kLaneRedBytes + kLaneWaves * lane_x_bytes<NB>();
-}
+// tables, partial sums, activation slots, and one word for the column-split hand-over
+template <int NB>
+__host__ __device__ constexpr int lane_flag_offset() { return kLaneTableBytes + NB * kLaneRedBytes + kLaneWaves * lane_x_bytes<NB>(); }
+template <int NB>
+__host__ __device__ constexpr int lane_lds_bytes() { return lane_flag_offset<NB>() + 16; }
 
 // x pair held by lane Q of the quad, times the looked-up pair, added to acc
 template <int Q>
@@ -402,8 +406,8 @@ constexpr int kLaneDepth = 2;
 // loads run kLaneDepth - 1 tiles ahead, also across row blocks; past the end of the run the ring is refilled with
 // dummy loads (see lane_load_tile).
 template <int K, int NB>
-__device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int split, int tid, char* lds,
-                                          int table_bytes) {
+__device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int split, int tid, char* lds) {
+  constexpr int table_bytes = kLaneTableBytes;
   constexpr int D = kLaneDepth<K, NB>;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const uint32_t lanecol = (uint32_t)lane * 4;  // the lane's column of the interleaved tables
@@ -477,39 +481,49 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       acc[b][0] = acc[b][1] = acc[b][2] = acc[b][3] = 0.f;
     }
     lane_group_barrier();
-    if (wave < NB && (NB == 1 || wave < job.nsamples)) {   // wavefront b stores sample b
-      float s = 0.f;
+    const bool storer = wave < NB && (NB == 1 || wave < job.nsamples);   // wavefront b stores sample b
+    float s = 0.f;
+    if (storer) {
 #pragma unroll
       for (int w = 0; w < kLaneWaves; ++w) s += red[(wave * kLaneWaves + w) * 64 + lane];
-      bool last = true;
-      if (nsplit > 1) {
-        // every workgroup of the row block leaves its sums, then takes a ticket; the holder of the last ticket
-        // finds all of them, adds them in the order of the splits and leaves the counter at zero again.  The sums
-        // are left with device-scope atomic exchanges and read with device-scope atomic loads: a read-modify-write
-        // is carried out where all dies see it, like the ticket itself, and has been carried out when its old
-        // value is back, so taking the ticket after that orders the two without writing back or invalidating a
-        // whole per-die cache (what a device-scope fence does, at several times the cost of the launch).  A
-        // store, atomic or not, is not enough: it is acknowledged before other dies see it (measured: under the
-        // memory traffic of concurrent GEMV workgroups one estimate in a few hundred came out with a stale sum).
-        DPLLM_GLOBAL float* part = as_global(job.ws) + (size_t)(rb * NB + wave) * nsplit * 64 + lane;
-        DPLLM_GLOBAL uint32_t* ticket = as_global(job.cnt) + rb * NB + wave;
-        const uint32_t before = __hip_atomic_exchange(reinterpret_cast<DPLLM_GLOBAL uint32_t*>(part + split * 64),
-                                                      __builtin_bit_cast(uint32_t, s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("" ::"v"(before));   // the old value is waited for: the exchange has been carried out
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        uint32_t old = 0;
-        if (lane == 0) old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last = __builtin_amdgcn_readfirstlane(old) == (uint32_t)(nsplit - 1);
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        if (last) {
-          s = 0.f;
-          for (int i = 0; i < nsplit; ++i) s += __hip_atomic_load(part + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if (lane == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-      }
-      const int o = rb * 64 + lane;
-      if (last && o < job.out) as_global(job.y)[(size_t)wave * job.out + o] = __builtin_bit_cast(uint16_t, (_Float16)s);
     }
+    bool last = true;
+    if (nsplit > 1) {
+      // Column split: every workgroup of the row block leaves its sums in the pool, then takes a ticket; the
+      // holder of the last ticket finds all of them, adds them in the order of the splits (so the result does
+      // not depend on who arrives last) and leaves the counter at zero again.  Ordering: plain stores ->
+      // workgroup barrier -> thread 0: release fence at agent scope, ticket (agent-scope read-modify-write),
+      // acquire fence at agent scope when the ticket is the last -> workgroup barrier -> plain loads.  The
+      // release fence writes the sums back to where every die sees them before the ticket is taken; the acquire
+      // fence drops what this die may still cache of the pool before the sums are read.
+      DPLLM_GLOBAL float* part = as_global(job.ws) + (size_t)(rb * NB + wave) * nsplit * 64 + lane;
+      DPLLM_GLOBAL uint32_t* ticket = as_global(job.cnt) + rb * NB;
+      uint32_t* flag = reinterpret_cast<uint32_t*>(lds + lane_flag_offset<NB>());
+      if (storer) part[split * 64] = s;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      if (tid == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool mine = old == (uint32_t)(nsplit - 1);
+        if (mine) {
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+          __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        *flag = mine;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      last = *flag != 0;
+      if (storer && last) {
+        s = 0.f;
+        for (int i = 0; i < nsplit; ++i) s += part[i * 64];
+      }
+    }
+    const int o = rb * 64 + lane;
+    if (storer && last && o < job.out) as_global(job.y)[(size_t)wave * job.out + o] = __builtin_bit_cast(uint16_t, (_Float16)s);
   };
   open_block();
   if (idle) {
@@ -542,29 +556,35 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   }
 }
 
-template <int KA, int KB, int NB>
+// The bitwidth of the job: its own value, or the word a selector left in device memory.  A value the linear
+// does not serve (outside [max(kmin, 3), p]) is not served: the workgroup returns and y keeps what it held.
+template <int NB>
 __device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, int tid, char* lds) {
   const int split = block % job.nsplit;
   block /= job.nsplit;
   if (block >= job.nrq) return;
-  constexpr int table_bytes = lane_table_bytes<KA, KB>();
-  if constexpr (KA != KB) {
-    if (job.k_dev != nullptr && __builtin_amdgcn_readfirstlane(*as_global(job.k_dev)) == KB) {
-      gemv_lane<KB, NB>(job, job.lut_off_b, block, split, tid, lds, table_bytes);
-      return;
-    }
+  int k = job.k;
+  if (job.k_dev != nullptr) k = __builtin_amdgcn_readfirstlane(*as_global(job.k_dev));
+  if (k < max(job.kmin, kFastKMin) || k > min(job.p, kFastKMax)) return;
+  switch (k) {   // (the table offsets are taken by constant index: a run-time index would put the job record in scratch memory)
+    case 3: gemv_lane<3, NB>(job, job.lut_off[0], block, split, tid, lds); break;
+    case 4: gemv_lane<4, NB>(job, job.lut_off[1], block, split, tid, lds); break;
+    case 5: gemv_lane<5, NB>(job, job.lut_off[2], block, split, tid, lds); break;
+    case 6: gemv_lane<6, NB>(job, job.lut_off[3], block, split, tid, lds); break;
+    case 7: gemv_lane<7, NB>(job, job.lut_off[4], block, split, tid, lds); break;
+    default: gemv_lane<8, NB>(job, job.lut_off[5], block, split, tid, lds); break;
   }
-  gemv_lane<KA, NB>(job, job.lut_off_a, block, split, tid, lds, table_bytes);
 }
 
 // jobs == nullptr: the job passed by value, for njobs right-hand sides in groups of NB that share one pass over
 // the planes (group g reads x + g * NB * in and writes y + g * NB * out; workgroups [g * nblocks, (g + 1) *
 // nblocks) serve it); else (NB = 1) block b belongs to job block_jobs[b] of the table
-template <int KA, int KB, int NB>
+template <int NB>
 __global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* __restrict__ jobs, const int32_t* __restrict__ block_jobs,
                                                                  int njobs, GemvJob one) {
-  // the tables sit at LDS address 0, which the lookup addresses assume
-  __shared__ __attribute__((aligned(16))) char lds[lane_lds_bytes<KA, KB, NB>()];
+  __shared__ __attribute__((aligned(256))) char lds[lane_lds_bytes<NB>()];
+  // the lookup addresses are formed as (entry << 8) | (lane << 2): the tables must start at LDS address 0
+  if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds != 0u) return;
   if (jobs == nullptr) {
     const int group = blockIdx.x / one.nblocks;
     one.x += (size_t)group * NB * one.ncw * 32;
@@ -572,13 +592,13 @@ __global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* 
     one.nsamples = min(NB, njobs - group * NB);
     one.ws += (size_t)group * one.nrq * NB * one.nsplit * 64;
     one.cnt += (size_t)group * one.nrq * NB;
-    gemv_lane_block<KA, KB, NB>(one, blockIdx.x - group * one.nblocks, threadIdx.x, lds);
+    gemv_lane_block<NB>(one, blockIdx.x - group * one.nblocks, threadIdx.x, lds);
     return;
   }
   if constexpr (NB == 1) {
     const int b = blockIdx.x;
     GemvJob job = jobs[block_jobs[b]];
-    gemv_lane_block<KA, KB, 1>(job, b - job.block_start, threadIdx.x, lds);
+    gemv_lane_block<1>(job, b - job.block_start, threadIdx.x, lds);
   }
 }
 

@@ -54,11 +54,9 @@ __host__ __device__ constexpr uint32_t field_mask(int period, int c, int width) 
 }
 
 // index (in 32-bit words, from the start of a plane) of the word holding columns 32 cw .. 32 cw + 31 of row o:
-// row-quad arrangement [row quad][word][4 rows]; row-per-lane arrangement [block of 64 rows][tile of 4 words]
-// [row][4 words]
-__host__ __device__ constexpr size_t plane_word_index(int row_lane, int o, int cw, int ncw, int ncc) {
-  return row_lane ? (((size_t)(o / 64) * ncc + cw / 4) * 64 + o % 64) * 4 + cw % 4
-                  : ((size_t)(o / 4) * ncw + cw) * 4 + o % 4;
+// [block of 64 rows][tile of 4 words][row][4 words]
+__host__ __device__ constexpr size_t plane_word_index(int o, int cw, int ncc) {
+  return (((size_t)(o / 64) * ncc + cw / 4) * 64 + o % 64) * 4 + cw % 4;
 }
 
 }  // namespace dpllm

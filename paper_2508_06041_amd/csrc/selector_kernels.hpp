@@ -3,15 +3,30 @@
 // alpha ||x|| + beta).  One launch serves a list of selector jobs; the bitwidth lands in device memory, where
 // the GEMV kernels read it.
 //
-// A job reads 0.5 - 3.5 MB of G.  It is cut into parts of 16 rows of G (one workgroup of four wavefronts,
-// four rows per wavefront sharing the activation loads) by a chunk of columns: the whole row when the launch
-// has enough parts to fill the chip, down to 512 columns when it serves a few linears only (a part that
-// streams a whole row alone takes 10 - 30 us).  A part leaves the fp64 partial dot products of its rows in
+// What a linear's selector is (candidate pair, estimator kind, G, alpha, beta, T) depends on the target
+// precision the model runs under (Algorithm 1 hands out one threshold list per target; Sec. 5.1 keeps one G per
+// candidate pair): the kernels read the number of the active target from device memory and take the linear's
+// parameters from the row of that target in a table, so that a switch of target is one word written on the
+// device and the launches stay what they are.
+//
+// A projection job reads 0.5 - 3.5 MB of G.  It is cut into parts of 16 rows of G (one workgroup of four
+// wavefronts, four rows per wavefront sharing the activation loads) by a chunk of columns: the whole row when
+// the launch has enough parts to fill the chip, down to 512 columns when it serves a few linears only (a part
+// that streams a whole row alone takes 10 - 30 us).  A part leaves the fp64 partial dot products of its rows in
 // workspace slots of its own and takes a ticket from the job's counter; the part that draws the last ticket
 // adds the partial products of every row in chunk order, squares, adds the rows in index order, takes the
 // square root and the decision, and leaves the counter at zero for the next launch.  The order of all
 // additions is fixed whichever part comes last.  (A separate kernel for this last step would cost a dependent
 // launch per group of linears that run together.)
+//
+// Hand-over between the parts: plain stores of the partial products -> workgroup barrier -> thread 0: release
+// fence at agent scope, then the ticket (an agent-scope read-modify-write); the thread that draws the last
+// ticket follows it with an acquire fence at agent scope -> workgroup barrier -> plain loads.  Every part's
+// stores happen before its ticket, every ticket before the last one's acquire: the last part sees them all.
+//
+// Linears whose estimator is the linear regression need sum x^2 only: the jobs of a launch that read the same
+// input vector form a group with one extra part, which adds up x^2 once (when any member asks for it) and takes
+// the decision of every member of kind "linear regression" or "none".
 //
 // The estimate and the compare are taken in fp64: fp16 x fp16 products are exact in fp32, their sum runs in
 // fp64 in a fixed order, so a decision is reproducible and differs from an ideal-arithmetic decision only
@@ -33,29 +48,34 @@ constexpr int kSelMaxRank = 1024;
 constexpr int kSelMaxChunks = 32;    // column chunks of a job
 constexpr int kSelChunkStep = 512;   // columns a wavefront covers per tile: chunks are multiples of it
 
-struct SelJob {
+// What the selector of one linear is under one target.  kind: 0 none (always l), 1 projection, 2 linear regression
+struct SelParams {
   const uint16_t* G;   // fp16 [r][in] (projection kind)
-  const uint16_t* x;   // fp16 [in]
+  float T, alpha, beta;
+  int32_t r, l, h, kind;
+  int32_t pad;
+};
+
+// The target-independent part of a selector job.
+struct SelJob {
+  const uint16_t* x;   // fp16 [in]: the vector the selector reads
   float* e_out;
   int32_t* k_out;
-  double* ws;          // projection: [nchunks][16 rowgroups] partial dot products; else one slot
+  double* ws;          // [nchunks][rows of G rounded up to 16] partial dot products
   uint32_t* ticket;    // arrival counter of this job, zero between launches
-  float T, alpha, beta;
-  int32_t in, r, l, h, kind;  // kind: 0 none, 1 projection, 2 linear regression
-  int32_t nparts;             // projection: rowgroups * nchunks; linear regression: 1; none: 1 (only the decision)
-  int32_t nchunks, chunk_cols;  // projection: part p covers rows [16 (p / nchunks), + 16), columns [chunk_cols (p % nchunks), + chunk_cols)
+  int32_t in;
+  int32_t linear;      // row of the job's linear in the parameter table
+  int32_t nchunks, chunk_cols;  // projection part p covers rows [16 (p / nchunks), + 16), columns [chunk_cols (p % nchunks), + chunk_cols)
+  int32_t ws_rows;     // rows of one chunk's slots in ws (the largest rank of the linear's pairs, rounded up to 16)
+  int32_t next;        // next job of the group that reads the same x in this launch (index in the launch's job table), -1: none
 };
 struct SelPart {
   int32_t job;    // index into the job table of the launch
-  int32_t part;   // part number inside the job: rows [16 part, 16 part + 16)
+  int32_t part;   // projection part number inside the job; -1: the group part of the group that starts at `job`
 };
 
 __host__ __device__ inline int sel_rowgroups_of(int kind, int r) {
-  return kind == 1 ? (r + kSelPartRows - 1) / kSelPartRows : 1;
-}
-// workspace slots (doubles) of a job
-__host__ __device__ inline int sel_slots_of(int kind, int r, int nchunks) {
-  return kind == 1 ? sel_rowgroups_of(kind, r) * kSelPartRows * nchunks : 1;
+  return kind == 1 ? (r + kSelPartRows - 1) / kSelPartRows : 0;
 }
 
 __device__ __forceinline__ double wave_sum_f64(double v) {
@@ -99,27 +119,39 @@ __device__ __forceinline__ void sel_accumulate(const SelTile& t, bool valid, dou
 }
 
 // the estimate from the sum of squares, and the decision
-__device__ __forceinline__ void selector_decide(const SelJob& job, double tot) {
+__device__ __forceinline__ void selector_decide(const SelJob& job, const SelParams& P, double tot) {
   double e = 0.0;
-  if (job.kind == 1) e = sqrt(tot);
-  else if (job.kind == 2) e = (double)job.alpha * sqrt(tot) + (double)job.beta;
+  if (P.kind == 1) e = sqrt(tot);
+  else if (P.kind == 2) e = (double)P.alpha * sqrt(tot) + (double)P.beta;
   *job.e_out = (float)e;
   // strictly exceeding T selects h; +inf pins l, -inf pins h; no estimator: always l
-  *job.k_out = (job.kind != 0 && e > (double)job.T) ? job.h : job.l;
+  *job.k_out = (P.kind != 0 && e > (double)P.T) ? P.h : P.l;
 }
 
-__device__ __forceinline__ void selector_part(const SelJob& job, int part, int tid) {
-  __shared__ double sq[kSelMaxRank];
-  __shared__ uint32_t is_last;
+// LDS of a selector workgroup
+struct SelShared {
+  double sq[kSelMaxRank];
+  uint32_t is_last;
+};
+
+// The group part: the decision of every member of the group whose estimator is "none" or the linear regression;
+// sum x^2 is added up once, when a member asks for it.  The member's parameters come from `params` (row of the
+// active target), or, for a lone job, from `one`.
+__device__ __forceinline__ void selector_group_part(const SelJob* jobs, int first, const SelParams* params, const SelJob& lone,
+                                                    const SelParams& one, int tid, SelShared& sh) {
   const int wave = tid >> 6, lane = tid & 63;
-  if (job.kind == 0) {   // no estimator: only the decision
-    if (tid == 0) selector_decide(job, 0.0);
-    return;
+  const SelJob& head = jobs ? jobs[first] : lone;
+  bool need = false;
+  if (jobs) {
+    for (int j = first; j >= 0; j = jobs[j].next) need = need || params[jobs[j].linear].kind == 2;
+  } else {
+    need = one.kind == 2;
   }
-  if (job.kind == 2) {   // sum of x^2, one part
+  double tot = 0.0;
+  if (need) {   // wavefront-uniform
     double acc = 0.0;
-    for (int c = tid * 8; c < job.in; c += kSelPartThreads * 8) {
-      uint4 xv = *reinterpret_cast<const uint4*>(job.x + c);
+    for (int c = tid * 8; c < head.in; c += kSelPartThreads * 8) {
+      const sel_u32x4 xv = *(const DPLLM_SEL_GLOBAL sel_u32x4*)(head.x + c);
       const __half* xh = reinterpret_cast<const __half*>(&xv);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -128,23 +160,35 @@ __device__ __forceinline__ void selector_part(const SelJob& job, int part, int t
       }
     }
     acc = wave_sum_f64(acc);
-    if (lane == 0) sq[wave] = acc;
+    if (lane == 0) sh.sq[wave] = acc;
     __syncthreads();
-    if (tid == 0) {
-      double tot = 0.0;
-      for (int w = 0; w < kSelPartWaves; ++w) tot += sq[w];
-      selector_decide(job, tot);
-    }
-    return;
+    for (int w = 0; w < kSelPartWaves; ++w) tot += sh.sq[w];
   }
-  // projection: wavefront w owns rows 16 rg + 4 w .. + 3 (clamped to r - 1; surplus rows are dropped), columns
-  // [cb, ce) of them
+  if (tid != 0) return;
+  if (jobs) {
+    for (int j = first; j >= 0; j = jobs[j].next) {
+      const SelParams P = params[jobs[j].linear];
+      if (P.kind != 1) selector_decide(jobs[j], P, tot);
+    }
+  } else if (one.kind != 1) {
+    selector_decide(lone, one, tot);
+  }
+}
+
+// One projection part: wavefront w owns rows 16 rg + 4 w .. + 3 (clamped to r - 1; surplus rows are dropped),
+// columns [cb, ce) of them
+__device__ __forceinline__ void selector_proj_part(const SelJob& job, const SelParams& P, int part, int tid, SelShared& sh) {
+  const int wave = tid >> 6, lane = tid & 63;
+  if (P.kind != 1) return;                                    // this target estimates the linear otherwise
   const int rg = part / job.nchunks, ch = part - rg * job.nchunks;
+  const int rowgroups = sel_rowgroups_of(1, P.r);
+  if (rg >= rowgroups) return;                                // the pair of this target has fewer rows of G
+  const int nparts = rowgroups * job.nchunks;
   const int cb = ch * job.chunk_cols, ce = min(job.in, cb + job.chunk_cols);
   const int row0 = rg * kSelPartRows + wave * kSelRowsPerWave;
   const uint16_t* rows[kSelRowsPerWave];
 #pragma unroll
-  for (int i = 0; i < kSelRowsPerWave; ++i) rows[i] = job.G + (size_t)min(row0 + i, job.r - 1) * job.in;
+  for (int i = 0; i < kSelRowsPerWave; ++i) rows[i] = P.G + (size_t)min(row0 + i, P.r - 1) * job.in;
   double acc[kSelRowsPerWave];
 #pragma unroll
   for (int i = 0; i < kSelRowsPerWave; ++i) acc[i] = 0.0;
@@ -171,58 +215,60 @@ __device__ __forceinline__ void selector_part(const SelJob& job, int part, int t
       ca = ca + kSelChunkStep >= cb + nit * kSelChunkStep ? ca + kSelChunkStep - nit * kSelChunkStep : ca + kSelChunkStep;
     }
   }
-  // The partial products are left with device-scope atomic exchanges and read with device-scope atomic loads.
-  // A read-modify-write is carried out where all dies see it, like the ticket itself, and has been carried out
-  // when its old value is back; a store, atomic or not, is acknowledged before other dies see it.  So every
-  // exchange is waited for before the ticket is taken, and whoever draws the last ticket finds all of them.
-  const int nrows = sel_rowgroups_of(1, job.r) * kSelPartRows;
   DPLLM_SEL_GLOBAL double* ws = (DPLLM_SEL_GLOBAL double*)job.ws;
   DPLLM_SEL_GLOBAL uint32_t* ticket = (DPLLM_SEL_GLOBAL uint32_t*)job.ticket;
-  double rowsum[kSelRowsPerWave];
 #pragma unroll
-  for (int i = 0; i < kSelRowsPerWave; ++i) rowsum[i] = wave_sum_f64(acc[i]);
-  if (lane == 0) {   // four exchanges in flight, one wait for their old values
-    unsigned long long before[kSelRowsPerWave];
-#pragma unroll
-    for (int i = 0; i < kSelRowsPerWave; ++i)
-      before[i] = __hip_atomic_exchange((DPLLM_SEL_GLOBAL unsigned long long*)(ws + (size_t)ch * nrows + row0 + i),
-                                        __builtin_bit_cast(unsigned long long, rowsum[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    static_assert(kSelRowsPerWave == 4, "the wait below names four values");
-    asm volatile("" ::"v"((uint32_t)before[0]), "v"((uint32_t)(before[0] >> 32)), "v"((uint32_t)before[1]), "v"((uint32_t)(before[1] >> 32)),
-                 "v"((uint32_t)before[2]), "v"((uint32_t)(before[2] >> 32)), "v"((uint32_t)before[3]), "v"((uint32_t)(before[3] >> 32)));
+  for (int i = 0; i < kSelRowsPerWave; ++i) {
+    const double rowsum = wave_sum_f64(acc[i]);
+    if (lane == 0) ws[(size_t)ch * job.ws_rows + row0 + i] = rowsum;
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();
+  __syncthreads();   // the four wavefronts' stores happen before thread 0's fence
   if (tid == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    is_last = old == (uint32_t)(job.nparts - 1);
+    const bool mine = old == (uint32_t)(nparts - 1);
+    if (mine) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // nobody else arrives in this launch
+    }
+    sh.is_last = mine;
   }
   __syncthreads();
-  if (!is_last) return;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-  for (int t = tid; t < job.r; t += kSelPartThreads) {
+  if (!sh.is_last) return;
+  for (int t = tid; t < P.r; t += kSelPartThreads) {
     double g = 0.0;
-    for (int c = 0; c < job.nchunks; ++c) g += __hip_atomic_load(ws + (size_t)c * nrows + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    sq[t] = g * g;
+    for (int c = 0; c < job.nchunks; ++c) g += ws[(size_t)c * job.ws_rows + t];
+    sh.sq[t] = g * g;
   }
   __syncthreads();
   if (tid == 0) {
-    __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     double tot = 0.0;
-    for (int t = 0; t < job.r; ++t) tot += sq[t];
-    selector_decide(job, tot);
+    for (int t = 0; t < P.r; ++t) tot += sh.sq[t];
+    selector_decide(job, P, tot);
   }
 }
 
-// parts == nullptr: the single job passed by value, workgroup b is its part b; else workgroup b serves parts[b]
-__global__ void __launch_bounds__(kSelPartThreads) selector_part_kernel(const SelJob* __restrict__ jobs,
-                                                                         const SelPart* __restrict__ parts, SelJob one) {
+// parts == nullptr: the single job `one_job` with the parameters `one`; workgroup b is its projection part b, or
+// (kinds "none" and "linear regression": one workgroup) its group part.  Else workgroup b serves parts[b] of the
+// launch's job table under the target *target.
+__global__ void __launch_bounds__(kSelPartThreads) selector_part_kernel(const SelJob* __restrict__ jobs, const SelPart* __restrict__ parts,
+                                                                         const SelParams* __restrict__ params,
+                                                                         const int32_t* __restrict__ target, int n_linears,
+                                                                         SelJob one_job, SelParams one) {
+  __shared__ SelShared sh;
   if (parts == nullptr) {
-    selector_part(one, blockIdx.x, threadIdx.x);
+    if (one.kind == 1) selector_proj_part(one_job, one, blockIdx.x, threadIdx.x, sh);
+    else selector_group_part(nullptr, 0, nullptr, one_job, one, threadIdx.x, sh);
+    return;
+  }
+  const SelPart p = parts[blockIdx.x];
+  const SelParams* row = params + (size_t)(*target) * n_linears;
+  if (p.part < 0) {
+    selector_group_part(jobs, p.job, row, one_job, one, threadIdx.x, sh);
   } else {
-    const SelPart p = parts[blockIdx.x];
-    SelJob job = jobs[p.job];
-    selector_part(job, p.part, threadIdx.x);
+    const SelJob job = jobs[p.job];
+    const SelParams P = row[job.linear];
+    selector_proj_part(job, P, p.part, threadIdx.x, sh);
   }
 }
 

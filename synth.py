@@ -4,6 +4,8 @@ This module only *makes inputs*: quantised linears in the canonical host layout,
 activation vectors, projection matrices G and thresholds.  It implements none
 of the hot path (no bitplane unpack, no GEMV, no selector) and is imported by
 neither the oracle nor the GPU library; both consume the arrays it returns.
+(build_model hands the generated arrays to a binding module it is given; it calls
+only that module's load and set_selector.)
 
 Recipe (shapes of Llama-class linears; stands in for trained weights and real
 activations, which are not available here):
@@ -154,6 +156,85 @@ LLAMA3_8B = [("q", 4096, 4096), ("k", 1024, 4096), ("v", 1024, 4096), ("o", 4096
              ("gate", 14336, 4096), ("up", 14336, 4096), ("down", 4096, 14336)]
 LLAMA_70B = [("q", 8192, 8192), ("k", 1024, 8192), ("v", 1024, 8192), ("o", 8192, 8192),
              ("gate", 28672, 8192), ("up", 28672, 8192), ("down", 8192, 28672)]
+
+
+def fit_linreg(xs: torch.Tensor, est: torch.Tensor):
+    """Least-squares (alpha, beta) of est ~ alpha * ||x||_2 + beta over the calibration activations: the
+    linear-regression estimator's constants (Sec. 5.1 of the paper), as fp32 values."""
+    nx = xs.double().norm(dim=1).cpu().numpy()
+    e = est.detach().cpu().numpy().astype(np.float64)
+    A = np.stack([nx, np.ones_like(nx)], axis=1)
+    (alpha, beta), *_ = np.linalg.lstsq(A, e, rcond=None)
+    return float(np.float32(alpha)), float(np.float32(beta))
+
+
+def linreg_estimates_fp64(xs: torch.Tensor, alpha: float, beta: float) -> torch.Tensor:
+    """Calibration-side alpha * ||x_t|| + beta (used only to place thresholds)."""
+    return alpha * xs.double().norm(dim=1) + beta
+
+
+def build_model(dp, shapes, n_blocks, p, pairs, n_x, seed=1234, keep_blocks=(0,), log=None, quantile=None, rank=64,
+                linreg_every=0, kmin=3):
+    """Harness helper: loads n_blocks x len(shapes) linears generated on the GPU into a model of the binding `dp`
+    and attaches, for every candidate pair of `pairs` ((l, h) tuples; the first one is left in use), one selector
+    per linear.  Thresholds: tau ~ U[0.05, 0.3] times the median of ||W_h x|| (default), or the `quantile` of the
+    calibration estimates (Phase 3 of Algorithm 1).  linreg_every = m > 0: the linears with index % m == m - 1 take
+    the linear-regression estimator (constants fitted to the calibration estimates), the others the projection.  Returns (model, meta); meta carries shapes, the activation
+    sets, per pair the selector constants and calibration estimates, and host copies of the linears of
+    `keep_blocks` for the oracle."""
+    import time
+    n = n_blocks * len(shapes)
+    model = dp.Model(n)
+    ins = sorted({in_ for _, _, in_ in shapes})
+    xs_by_in = {in_: make_x(in_, n_x, seed=seed + in_, device="cuda") for in_ in ins}
+    rng = np.random.default_rng(seed)
+    taus = rng.uniform(0.05, 0.3, size=n)
+    meta = {"shapes": [], "xs_by_in": xs_by_in, "host": {}, "pairs": list(pairs),
+            "sel": {pr: [] for pr in pairs}}      # sel[(l,h)][i] = dict(kind, G, alpha, beta, T, est)
+    t0 = time.time()
+    for b in range(n_blocks):
+        for j, (name, out, in_) in enumerate(shapes):
+            i = b * len(shapes) + j
+            lin = make_linear(out, in_, p, kmin, seed=seed + 7919 * i, device="cuda", keep_codes=True)
+            model.dpllm_load_linear(i, lin["planes"], lin["luts"], kmin)
+            xs = xs_by_in[in_]
+            for pi, (l, h) in reversed(list(enumerate(pairs))):      # the first pair is attached last: it stays in use
+                G = make_G(lin, l, h, rank, seed=seed + 104729 * i + 1 + pi)
+                est = estimates_fp64(G, xs)
+                kind, alpha, beta = 1, 0.0, 0.0
+                if linreg_every and i % linreg_every == linreg_every - 1:
+                    kind = 2
+                    alpha, beta = fit_linreg(xs, est)
+                    est = linreg_estimates_fp64(xs, alpha, beta)
+                    G = None
+                if quantile is None:
+                    T = thresholds_from_tau(lin, h, xs, float(taus[i]))
+                    if kind == 2:       # the fitted line is nearly flat on these activations: split its range
+                        T = float(est.median())
+                else:   # Phase-3 style: the rho-quantile of the calibration estimates
+                    T = quantile_threshold(est, quantile)
+                T = nudge_threshold(T, est, band=1e-6)
+                model.dpllm_set_selector(i, l, h, kind, G=G, alpha=alpha, beta=beta, T=T)
+                meta["sel"][(l, h)].append(None)
+                meta["sel"][(l, h)][-1] = {"kind": kind, "G": G, "alpha": alpha, "beta": beta, "T": T, "est": est}
+            meta["shapes"].append((out, in_))
+            if b in keep_blocks:
+                meta["host"][i] = {"planes": planes_np(lin["planes"]),
+                                   "luts": {k: lut_np(v) for k, v in lin["luts"].items()}}
+            del lin
+        if log and (b % 8 == 7 or b == n_blocks - 1):
+            log("built block %d/%d (%.0f s)" % (b + 1, n_blocks, time.time() - t0))
+    return model, meta
+
+
+def oracle_selector(meta, pair, i, T=None):
+    """The selector dict the oracle's decode_step takes, for linear i under candidate pair `pair`."""
+    s = meta["sel"][pair][i]
+    d = {"l": pair[0], "h": pair[1], "kind": s["kind"], "alpha": s["alpha"], "beta": s["beta"],
+         "T": s["T"] if T is None else T}
+    if s["G"] is not None:
+        d["G"] = lut_np(s["G"])
+    return d
 
 
 def to_np(t: torch.Tensor) -> np.ndarray:

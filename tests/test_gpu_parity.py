@@ -16,19 +16,12 @@ REL_L2 = 2e-3          # tolerance of the GEMV output stated for this path
 DECISION_BAND = 1e-9   # decisions must agree wherever |e - T| exceeds this relative band
 
 
-@pytest.fixture(scope="module", params=["rowquad", "rowlane"])
-def dp(request):
-    """The binding, with every model of the test created in one of the two plane arrangements."""
-    import os
+@pytest.fixture(scope="module")
+def dp():
+    """The binding (importing it loads the HIP library; there is no other path)."""
     import paper_2508_06041_amd as dp
     assert torch.cuda.is_available()
-    old = os.environ.get("DPLLM_LAYOUT")
-    os.environ["DPLLM_LAYOUT"] = request.param
-    yield dp
-    if old is None:
-        del os.environ["DPLLM_LAYOUT"]
-    else:
-        os.environ["DPLLM_LAYOUT"] = old
+    return dp
 
 
 def rel_l2(got, ref):
@@ -384,6 +377,157 @@ def test_decode_step_under_graph_capture_replays(dp):
         assert torch.equal(k_dev, eager_k) and torch.equal(e_dev, eager_e)
         for y, ey in zip(ys, eager_y):
             assert torch.equal(y, ey)
+    model.close()
+
+
+def _mixed_kind_model(dp, shapes, p, pairs, n_steps, seed):
+    """Small model whose linears hold several candidate pairs and all three selector kinds: index % 3 == 0 the
+    projection, 1 the linear regression, 2 none for the pair (l, l) (a layer pinned to one bitwidth)."""
+    model = dp.Model(len(shapes))
+    xs_by_in = {in_: synth.make_x(in_, n_steps, seed=seed + in_) for _, in_ in shapes}
+    # activation norms that differ from step to step, so that the linear regression has something to decide on
+    for in_ in xs_by_in:
+        scale = torch.linspace(0.5, 2.0, n_steps)[torch.randperm(n_steps, generator=torch.Generator().manual_seed(seed))]
+        xs_by_in[in_] = (xs_by_in[in_].float() * scale[:, None]).half()
+    refs = []
+    for i, (out, in_) in enumerate(shapes):
+        lin = synth.make_linear(out, in_, p, 3, seed=seed + 13 * i)
+        model.dpllm_load_linear(i, synth.planes_np(lin["planes"]),
+                                {k: synth.lut_np(v) for k, v in lin["luts"].items()}, 3)
+        sels = {}
+        for l, h in reversed(pairs):
+            xs = xs_by_in[in_]
+            if i % 3 == 0:
+                G = synth.make_G(lin, l, h, 64 if l == 3 else 40, seed=seed + 17 * i + l)
+                est = synth.estimates_fp64(G, xs)
+                sel = {"l": l, "h": h, "kind": 1, "G": synth.lut_np(G), "alpha": 0.0, "beta": 0.0}
+                model.dpllm_set_selector(i, l, h, dp.DPLLM_SEL_PROJ, G=G.cuda(), T=0.0)
+            elif i % 3 == 1:
+                alpha, beta = 0.25 + 0.05 * i, -1.0
+                est = synth.linreg_estimates_fp64(xs, alpha, beta)
+                sel = {"l": l, "h": h, "kind": 2, "alpha": alpha, "beta": beta}
+                model.dpllm_set_selector(i, l, h, dp.DPLLM_SEL_LINREG, alpha=alpha, beta=beta, T=0.0)
+            else:
+                est = None
+                sel = {"l": l, "h": l, "kind": 0, "alpha": 0.0, "beta": 0.0}
+                model.dpllm_set_selector(i, l, l, dp.DPLLM_SEL_NONE)
+            sel["est"] = est
+            sels[(l, h)] = sel
+        refs.append({"planes": synth.planes_np(lin["planes"]),
+                     "luts": {k: synth.lut_np(v) for k, v in lin["luts"].items()}, "sels": sels})
+    return model, refs, xs_by_in
+
+
+def _threshold(sel, rho):
+    if sel["est"] is None:
+        return 0.0
+    return synth.nudge_threshold(synth.quantile_threshold(sel["est"], rho), sel["est"], band=1e-6)
+
+
+def _oracle_step(refs, pair, Ts, x_np):
+    lins = []
+    for ref, T in zip(refs, Ts):
+        s = dict(ref["sels"][pair])
+        s["T"] = T
+        lins.append({"planes": ref["planes"], "luts": ref["luts"], "selector": s})
+    return oracle.decode_step(lins, x_np)
+
+
+def test_decode_step_mixed_selector_kinds(dp):
+    """One step launch with projection, linear-regression and no-estimator linears side by side; linears that
+    read the same vector share one pass over x^2 (Sec. 5.1: about half the layers take the linear regression).
+    Estimates, decisions and outputs against the oracle on every step."""
+    shapes = [(128, 256), (128, 256), (64, 256), (128, 128), (320, 256), (320, 256), (256, 320), (96, 320), (64, 128)]
+    n_steps = 10
+    model, refs, xs_by_in = _mixed_kind_model(dp, shapes, 5, [(3, 4)], n_steps, seed=7300)
+    n = len(shapes)
+    Ts = [_threshold(r["sels"][(3, 4)], 0.5) for r in refs]
+    for i, r in enumerate(refs):
+        s = r["sels"][(3, 4)]
+        if s["kind"]:
+            model.dpllm_set_threshold(i, s["l"], s["h"], Ts[i])
+    k_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(n, dtype=torch.float32, device="cuda")
+    seen = {1: set(), 2: set()}
+    for t in range(n_steps):
+        xs = [xs_by_in[in_][t].cuda() for _, in_ in shapes]
+        ys = [torch.empty(out, dtype=torch.float16, device="cuda") for out, _ in shapes]
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+        torch.cuda.synchronize()
+        ry, rk, re = _oracle_step(refs, (3, 4), Ts, [synth.lut_np(xs_by_in[in_][t]) for _, in_ in shapes])
+        for i in range(n):
+            kind = refs[i]["sels"][(3, 4)]["kind"]
+            if kind:
+                assert abs(re[i] - Ts[i]) > DECISION_BAND * max(abs(Ts[i]), abs(re[i])), (i, t)
+                seen[kind].add(int(rk[i]))
+        assert k_dev.cpu().numpy().tolist() == rk.tolist(), t
+        assert np.allclose(e_dev.cpu().numpy(), re, rtol=3e-7, atol=0), t
+        for y, r in zip(ys, ry):
+            assert rel_l2(y.float().cpu().numpy(), r) <= REL_L2
+    assert seen[1] == {3, 4} and seen[2] == {3, 4}
+    model.close()
+
+
+def test_target_switch_between_graph_replays(dp):
+    """Run-time adaptation (Sec. 2.1; Algorithm 1: one threshold list per target; Sec. 5.1: one G per pair): three
+    targets resident -- (3,4) at the median threshold, (4,5) at the median, (3,4) at the 0.75 quantile -- and one
+    captured step.  dpllm_set_target switches between replays with one device word; every replay must give the
+    oracle's decisions, estimates and outputs for the target in force, and rebuild nothing."""
+    shapes = [(128, 256), (128, 256), (64, 256), (128, 128), (320, 256), (320, 256), (256, 320)]
+    n_steps = 8
+    pairs = [(3, 4), (4, 5)]
+    model, refs, xs_by_in = _mixed_kind_model(dp, shapes, 5, pairs, n_steps, seed=8400)
+    n = len(shapes)
+    targets = {0: ((3, 4), 0.5), 1: ((4, 5), 0.5), 2: ((3, 4), 0.75)}
+    T_of = {}
+    for t, (pair, rho) in targets.items():
+        T_of[t] = [_threshold(r["sels"][pair], rho) for r in refs]
+        for i, r in enumerate(refs):
+            s = r["sels"][pair]
+            if t == 0:
+                if s["kind"]:
+                    model.dpllm_set_threshold(i, s["l"], s["h"], T_of[t][i])
+            else:
+                model.dpllm_set_target_entry(t, i, s["l"], s["h"], T_of[t][i])
+    xbuf = {in_: torch.zeros(in_, dtype=torch.float16, device="cuda") for in_ in xs_by_in}
+    xs = [xbuf[in_] for _, in_ in shapes]
+    ys = [torch.zeros(out, dtype=torch.float16, device="cuda") for out, _ in shapes]
+    k_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    e_dev = torch.zeros(n, dtype=torch.float32, device="cuda")
+    for in_ in xbuf:
+        xbuf[in_].copy_(xs_by_in[in_][0])
+    model.dpllm_decode_step(xs, ys, k_dev, e_dev)      # builds the plan and copies the tables (not capturable)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+    seen = {t: set() for t in targets}
+    for step, t in enumerate([0, 1, 2, 2, 0, 1, 0, 2]):
+        model.dpllm_set_target(t)
+        for in_ in xbuf:
+            xbuf[in_].copy_(xs_by_in[in_][step])
+        for y in ys:
+            y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        pair = targets[t][0]
+        ry, rk, re = _oracle_step(refs, pair, T_of[t], [synth.lut_np(xs_by_in[in_][step]) for _, in_ in shapes])
+        for i in range(n):
+            if refs[i]["sels"][pair]["kind"]:
+                assert abs(re[i] - T_of[t][i]) > DECISION_BAND * max(abs(T_of[t][i]), abs(re[i])), (i, step)
+        assert k_dev.cpu().numpy().tolist() == rk.tolist(), (step, t)
+        assert np.allclose(e_dev.cpu().numpy(), re, rtol=3e-7, atol=0), (step, t)
+        for y, r in zip(ys, ry):
+            assert rel_l2(y.float().cpu().numpy(), r) <= REL_L2, (step, t)
+        seen[t].update(rk.tolist())
+    assert seen[0] >= {3, 4} and seen[1] >= {4, 5} and seen[2] >= {3, 4}
+    # the same switches with eager steps
+    for step, t in enumerate([1, 0]):
+        model.dpllm_set_target(t)
+        model.dpllm_decode_step(xs, ys, k_dev, e_dev)
+        torch.cuda.synchronize()
+        _, rk, _ = _oracle_step(refs, targets[t][0], T_of[t], [synth.lut_np(xs_by_in[in_][7]) for _, in_ in shapes])
+        assert k_dev.cpu().numpy().tolist() == rk.tolist(), (step, t)
     model.close()
 
 
