@@ -76,6 +76,8 @@ struct Phase {
   int blocks = 0;                       // workgroups of that launch
   int block_first = 0;                  // slice of the device workgroup-to-job table
   std::vector<int> plain;               // linears served by the plain kernel, one launch each
+  bool decide = false;                  // a linear of the selector launch is served by the plain kernel, which reads its
+                                        // bitwidth from k_dev: the decisions of this launch are taken by a launch of their own
 };
 constexpr int kLanePoolRows = 8192;     // row blocks x splits of the column-split launches that may be in flight
 constexpr size_t kSelOneSlots = (size_t)kSelMaxChunks * kSelMaxRank;
@@ -95,10 +97,10 @@ struct Workspace {
   char* base = nullptr;
   size_t bytes = 0;
   size_t lane_ws = 0, lane_cnt = 0;          // column-split pool: kLanePoolRows x 64 fp32, kLanePoolRows counters
-  size_t est_ws = 0, est_ticket = 0;         // dpllm_estimate: kSelOneSlots fp64, one counter
+  size_t est_ws = 0;                         // dpllm_estimate: kSelOneSlots fp64
   size_t target = 0;                         // the number of the active target
   size_t sel_params = 0;                     // SelParams [DPLLM_MAX_TARGETS][n]
-  size_t sel_jobs = 0, sel_tickets = 0;      // SelJob [n], counters [n]
+  size_t sel_jobs = 0;                       // SelJob [n]
   size_t sel_parts = 0, sel_parts_cap = 0;   // SelPart [cap]
   size_t sel_ws = 0, sel_ws_cap = 0;         // fp64 [cap]
   size_t gemv_jobs = 0;                      // GemvJob [n]
@@ -182,11 +184,9 @@ Workspace carve_workspace(const dpllm_model* m) {
   w.lane_ws = take(sizeof(float) * 64 * kLanePoolRows);
   w.lane_cnt = take(sizeof(uint32_t) * kLanePoolRows);
   w.est_ws = take(sizeof(double) * kSelOneSlots);
-  w.est_ticket = take(sizeof(uint32_t));
   w.target = take(sizeof(int32_t));
   w.sel_params = take(sizeof(SelParams) * DPLLM_MAX_TARGETS * n);
   w.sel_jobs = take(sizeof(SelJob) * n);
-  w.sel_tickets = take(sizeof(uint32_t) * n);
   w.sel_parts_cap = parts;
   w.sel_parts = take(sizeof(SelPart) * parts);
   w.sel_ws_cap = slots;
@@ -216,7 +216,6 @@ SelJob make_sel_job(const Linear& lin, int linear, int rowgroups, const void* x,
   j.e_out = e_dev;
   j.k_out = k_dev;
   j.ws = nullptr;
-  j.ticket = nullptr;
   j.in = lin.L.in;
   j.linear = linear;
   j.nchunks = 1;
@@ -243,6 +242,8 @@ GemvJob make_gemv_job(const Linear& lin, int k, const int32_t* k_dev, const void
   j.x = (const uint16_t*)x;
   j.y = (uint16_t*)y;
   j.k_dev = k_dev;
+  j.has_fin = 0;
+  j.fin = SelFinish{};
   j.plane_stride_u4 = (uint32_t)(lin.L.plane_bytes / 16);
   for (int kk = kFastKMin; kk <= kFastKMax; ++kk)
     j.lut_off[kk - kFastKMin] = (kk >= lin.L.kmin && kk <= lin.L.p) ? (uint32_t)lin.L.lut_offset[kk] : 0u;
@@ -331,10 +332,10 @@ int launch_gemv(dpllm_model* m, const Linear& lin, int k, const int32_t* k_dev, 
   }
   if (B > 1)
     hipLaunchKernelGGL((gemv_lane_kernel<2>), dim3(j.nblocks * (unsigned)groups), dim3(kLaneThreads), 0, st, (const GemvJob*)nullptr,
-                       (const int32_t*)nullptr, B, j);
+                       (const int32_t*)nullptr, B, j, (const SelParams*)nullptr, (const int32_t*)nullptr, 0);
   else
     hipLaunchKernelGGL((gemv_lane_kernel<1>), dim3(j.nblocks), dim3(kLaneThreads), 0, st, (const GemvJob*)nullptr,
-                       (const int32_t*)nullptr, 1, j);
+                       (const int32_t*)nullptr, 1, j, (const SelParams*)nullptr, (const int32_t*)nullptr, 0);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -434,6 +435,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     }
     sel_of_phase[q].push_back(j);
   }
+  std::vector<int> sel_job_of(n, -1);   // index of every linear's selector job (it sits in its own phase or an earlier one)
   for (size_t pi = 0; pi < bounds.size(); ++pi) {
     long pool_used = 0;   // phases follow one another on the stream: each may use the whole partial-sum pool
     const int id = bounds[pi].first, end = bounds[pi].second;
@@ -450,8 +452,9 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       SelJob sj = make_sel_job(lin, j, rowgroups, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j, launch_rowgroups);
       for (int part = 0; part < rowgroups * sj.nchunks; ++part) sel_parts.push_back(SelPart{(int)local, part});
       sj.ws = W.at<double>(W.sel_ws) + ws_slots;
-      sj.ticket = W.at<uint32_t>(W.sel_tickets) + sel_jobs.size();
       ws_slots += (size_t)sj.ws_rows * sj.nchunks;
+      sel_job_of[j] = (int)sel_jobs.size();
+      if (!lin.streaming()) ph.decide = true;
       sel_jobs.push_back(sj);
     }
     // groups of jobs that read the same vector: one more part each, which takes the decisions that need no
@@ -500,6 +503,8 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       const Linear& lin = m->linears[j];
       if (!lin.streaming()) { ph.plain.push_back(j); continue; }
       GemvJob gj = make_gemv_job(lin, 0, k_dev + j, xs[j], ys[j]);
+      gj.has_fin = 1;
+      gj.fin = sel_finish_of(sel_jobs[sel_job_of[j]]);
       long group_bytes = kLaneGroupBytes;
       if (taper && bytes_after[j - id] < 512 * kLaneGroupBytes) group_bytes /= 2;
       const int rpb = pick_blocks_per_group(lin.L, lin.part_k(), total_rq, group_bytes);
@@ -589,8 +594,7 @@ int dpllm_set_workspace(dpllm_model* m, void* ws_dev, size_t bytes, void* stream
   w.bytes = bytes;
   hipStream_t st = (hipStream_t)stream;
   // counters and the target word start at zero; everything else is written before it is read
-  const size_t n = m->linears.size();
-  struct { size_t off, words; } zero[] = {{w.lane_cnt, (size_t)kLanePoolRows}, {w.est_ticket, 1}, {w.target, 1}, {w.sel_tickets, n}};
+  struct { size_t off, words; } zero[] = {{w.lane_cnt, (size_t)kLanePoolRows}, {w.target, 1}};
   for (const auto& z : zero)
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((z.words + 255) / 256)), dim3(256), 0, st, w.at<uint32_t>(z.off), z.words, 0u);
   HIP_TRY(m, hipGetLastError());
@@ -769,10 +773,13 @@ int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, floa
   const int rowgroups = sel_rowgroups_of(sel.kind, sel.r);
   SelJob j = make_sel_job(*lin, id, rowgroups, x_dev, e_dev, k_dev, rowgroups);
   j.ws = m->ws.at<double>(m->ws.est_ws);
-  j.ticket = m->ws.at<uint32_t>(m->ws.est_ticket);
-  const int blocks = sel.kind == DPLLM_SEL_PROJ ? rowgroups * j.nchunks : 1;
-  hipLaunchKernelGGL(selector_part_kernel, dim3(blocks), dim3(kSelPartThreads), 0, (hipStream_t)stream, (const SelJob*)nullptr,
-                     (const SelPart*)nullptr, (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, make_params(sel, sel.T));
+  const SelParams P = make_params(sel, sel.T);
+  const int blocks = sel.kind == DPLLM_SEL_PROJ ? rowgroups * j.nchunks : sel.kind == DPLLM_SEL_LINREG ? 1 : 0;
+  if (blocks > 0)
+    hipLaunchKernelGGL(selector_part_kernel, dim3(blocks), dim3(kSelPartThreads), 0, (hipStream_t)stream, (const SelJob*)nullptr,
+                       (const SelPart*)nullptr, (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, P);
+  hipLaunchKernelGGL(selector_decide_kernel, dim3(1), dim3(kSelDecideThreads), 0, (hipStream_t)stream, (const SelJob*)nullptr,
+                     (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, P);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
 }
@@ -827,16 +834,24 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
   SelJob none{};
   SelParams pnone{};
   GemvJob gnone{};
+  const SelParams* d_params = W.at<SelParams>(W.sel_params);
+  const int32_t* d_target = W.at<int32_t>(W.target);
+  const bool both = parts == (DPLLM_STEP_SELECT | DPLLM_STEP_GEMV);
   for (const Phase& ph : P.phases) {
-    if ((parts & DPLLM_STEP_SELECT) && ph.part_count > 0)
-      hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st,
-                         (const SelJob*)(W.at<SelJob>(W.sel_jobs) + ph.sel_first), (const SelPart*)(W.at<SelPart>(W.sel_parts) + ph.part_first),
-                         (const SelParams*)W.at<SelParams>(W.sel_params), (const int32_t*)W.at<int32_t>(W.target), n, none, pnone);
+    if ((parts & DPLLM_STEP_SELECT) && ph.sel_count > 0) {
+      const SelJob* jobs = W.at<SelJob>(W.sel_jobs) + ph.sel_first;
+      hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
+                         (const SelPart*)(W.at<SelPart>(W.sel_parts) + ph.part_first), d_params, d_target, n, none, pnone);
+      // Whole step: the GEMV workgroups take the decisions of their linears themselves.  Selectors alone, or a
+      // linear on the plain kernel: a launch that finishes every job of this selector launch.
+      if (!both || ph.decide)
+        hipLaunchKernelGGL(selector_decide_kernel, dim3(ph.sel_count), dim3(kSelDecideThreads), 0, st, jobs, d_params, d_target, n, none, pnone);
+    }
     if (!(parts & DPLLM_STEP_GEMV)) continue;
     if (ph.gemv_count > 0)
       hipLaunchKernelGGL((gemv_lane_kernel<1>), dim3(ph.blocks), dim3(kLaneThreads), 0, st,
                          (const GemvJob*)(W.at<GemvJob>(W.gemv_jobs) + ph.gemv_first), (const int32_t*)(W.at<int32_t>(W.block_jobs) + ph.block_first),
-                         ph.gemv_count, gnone);
+                         ph.gemv_count, gnone, both ? d_params : (const SelParams*)nullptr, d_target, n);
     for (int j : ph.plain) {
       int rc = launch_plain(m, m->linears[j], 0, k_dev + j, xs[j], ys[j], 1, st);
       if (rc != DPLLM_OK) return rc;

@@ -17,6 +17,7 @@
 #include <cstdint>
 
 #include "layout_device.hpp"
+#include "selector_kernels.hpp"
 
 namespace dpllm {
 
@@ -31,6 +32,11 @@ struct GemvJob {
   const uint16_t* x;          // fp16 [in]
   uint16_t* y;                // fp16 [out]
   const int32_t* k_dev;       // nullptr: serve k; else the bitwidth is *k_dev (written by a selector)
+  // has_fin != 0: neither; the bitwidth is decided in the workgroup's prologue from the partial results an earlier
+  // selector launch left in the workspace (selector_finish), and the job's first workgroup writes it and the
+  // estimate to the caller's arrays
+  int32_t has_fin;
+  SelFinish fin;
   uint32_t plane_stride_u4;
   uint32_t lut_off[kFastKMax - kFastKMin + 1];  // byte offset of the k-bit table inside the arena, k = 3..8
   int32_t k;                  // the bitwidth when k_dev == nullptr

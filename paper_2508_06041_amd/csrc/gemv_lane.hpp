@@ -556,15 +556,25 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   }
 }
 
-// The bitwidth of the job: its own value, or the word a selector left in device memory.  A value the linear
-// does not serve (outside [max(kmin, 3), p]) is not served: the workgroup returns and y keeps what it held.
+// The bitwidth of the job: its own value, the word a selector left in device memory, or the decision taken here
+// from the partial results of an earlier selector launch (every workgroup of the job repeats the same fixed-order
+// sums, so all arrive at the same bits; the job's first workgroup writes bitwidth and estimate out).  A value the
+// linear does not serve (outside [max(kmin, 3), p]) is not served: the workgroup returns and y keeps what it held.
 template <int NB>
-__device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, int tid, char* lds) {
+__device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, int tid, char* lds, const SelParams* params,
+                                                const int32_t* target, int n_linears) {   // params == nullptr: no decisions here
+  const int first = block == 0;
   const int split = block % job.nsplit;
   block /= job.nsplit;
   if (block >= job.nrq) return;
   int k = job.k;
-  if (job.k_dev != nullptr) k = __builtin_amdgcn_readfirstlane(*as_global(job.k_dev));
+  if (job.has_fin && params != nullptr) {
+    const SelParams P = params[(size_t)(*target) * n_linears + job.fin.linear];
+    k = selector_finish(job.fin, P, tid, kLaneThreads, reinterpret_cast<double*>(lds), first);   // the tables are not built yet
+    k = __builtin_amdgcn_readfirstlane(k);
+  } else if (job.k_dev != nullptr) {
+    k = __builtin_amdgcn_readfirstlane(*as_global(job.k_dev));
+  }
   if (k < max(job.kmin, kFastKMin) || k > min(job.p, kFastKMax)) return;
   switch (k) {   // (the table offsets are taken by constant index: a run-time index would put the job record in scratch memory)
     case 3: gemv_lane<3, NB>(job, job.lut_off[0], block, split, tid, lds); break;
@@ -578,10 +588,12 @@ __device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, i
 
 // jobs == nullptr: the job passed by value, for njobs right-hand sides in groups of NB that share one pass over
 // the planes (group g reads x + g * NB * in and writes y + g * NB * out; workgroups [g * nblocks, (g + 1) *
-// nblocks) serve it); else (NB = 1) block b belongs to job block_jobs[b] of the table
+// nblocks) serve it); else (NB = 1) block b belongs to job block_jobs[b] of the table.  params / target /
+// n_linears: the table of selector parameters, for jobs that take their decision here.
 template <int NB>
 __global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* __restrict__ jobs, const int32_t* __restrict__ block_jobs,
-                                                                 int njobs, GemvJob one) {
+                                                                 int njobs, GemvJob one, const SelParams* __restrict__ params,
+                                                                 const int32_t* __restrict__ target, int n_linears) {
   __shared__ __attribute__((aligned(256))) char lds[lane_lds_bytes<NB>()];
   // the lookup addresses are formed as (entry << 8) | (lane << 2): the tables must start at LDS address 0
   if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds != 0u) return;
@@ -592,13 +604,13 @@ __global__ void __launch_bounds__(kLaneThreads) gemv_lane_kernel(const GemvJob* 
     one.nsamples = min(NB, njobs - group * NB);
     one.ws += (size_t)group * one.nrq * NB * one.nsplit * 64;
     one.cnt += (size_t)group * one.nrq * NB;
-    gemv_lane_block<NB>(one, blockIdx.x - group * one.nblocks, threadIdx.x, lds);
+    gemv_lane_block<NB>(one, blockIdx.x - group * one.nblocks, threadIdx.x, lds, params, target, n_linears);
     return;
   }
   if constexpr (NB == 1) {
     const int b = blockIdx.x;
     GemvJob job = jobs[block_jobs[b]];
-    gemv_lane_block<1>(job, b - job.block_start, threadIdx.x, lds);
+    gemv_lane_block<1>(job, b - job.block_start, threadIdx.x, lds, params, target, n_linears);
   }
 }
 

@@ -13,20 +13,20 @@
 // wavefronts, four rows per wavefront sharing the activation loads) by a chunk of columns: the whole row when
 // the launch has enough parts to fill the chip, down to 512 columns when it serves a few linears only (a part
 // that streams a whole row alone takes 10 - 30 us).  A part leaves the fp64 partial dot products of its rows in
-// workspace slots of its own and takes a ticket from the job's counter; the part that draws the last ticket
-// adds the partial products of every row in chunk order, squares, adds the rows in index order, takes the
-// square root and the decision, and leaves the counter at zero for the next launch.  The order of all
-// additions is fixed whichever part comes last.  (A separate kernel for this last step would cost a dependent
-// launch per group of linears that run together.)
+// workspace slots of its own, and that is all it does.  Linears whose estimator is the linear regression need
+// sum x^2 only: the jobs of a launch that read the same input vector form a group with one extra part, which
+// adds up x^2 once and leaves it in the slot of every member that asks for it.
 //
-// Hand-over between the parts: plain stores of the partial products -> workgroup barrier -> thread 0: release
-// fence at agent scope, then the ticket (an agent-scope read-modify-write); the thread that draws the last
-// ticket follows it with an acquire fence at agent scope -> workgroup barrier -> plain loads.  Every part's
-// stores happen before its ticket, every ticket before the last one's acquire: the last part sees them all.
-//
-// Linears whose estimator is the linear regression need sum x^2 only: the jobs of a launch that read the same
-// input vector form a group with one extra part, which adds up x^2 once (when any member asks for it) and takes
-// the decision of every member of kind "linear regression" or "none".
+// The estimate and the decision are taken by whoever consumes them, in a LATER launch on the same stream
+// (selector_finish): the GEMV kernel, in the prologue of every workgroup of the linear (the first one also
+// writes the estimate and the bitwidth to the caller's arrays), or selector_decide_kernel where no GEMV follows.
+// The end of the launch that wrote the partial products and the start of the one that reads them order the two
+// at device scope; no workgroup waits for another inside a launch.  (Handing the partial products to a last-
+// arriving part inside the launch needs a device-scope release by every part and an acquire by the last one;
+// the release writes back the die's whole L2 and measured 126 us for the 224 selectors of a 7B step, against
+// 30 us for the parts alone.)  selector_finish adds the partial products of every row in chunk order, squares,
+// adds the rows in index order, takes the square root and compares: the order of all additions is fixed, so every
+// workgroup that repeats it gets the same bits.
 //
 // The estimate and the compare are taken in fp64: fp16 x fp16 products are exact in fp32, their sum runs in
 // fp64 in a fixed order, so a decision is reproducible and differs from an ideal-arithmetic decision only
@@ -61,8 +61,7 @@ struct SelJob {
   const uint16_t* x;   // fp16 [in]: the vector the selector reads
   float* e_out;
   int32_t* k_out;
-  double* ws;          // [nchunks][rows of G rounded up to 16] partial dot products
-  uint32_t* ticket;    // arrival counter of this job, zero between launches
+  double* ws;          // [nchunks][ws_rows] partial dot products (projection), or [0] = sum x^2 (linear regression)
   int32_t in;
   int32_t linear;      // row of the job's linear in the parameter table
   int32_t nchunks, chunk_cols;  // projection part p covers rows [16 (p / nchunks), + 16), columns [chunk_cols (p % nchunks), + chunk_cols)
@@ -118,25 +117,53 @@ __device__ __forceinline__ void sel_accumulate(const SelTile& t, bool valid, dou
   }
 }
 
-// the estimate from the sum of squares, and the decision
-__device__ __forceinline__ void selector_decide(const SelJob& job, const SelParams& P, double tot) {
-  double e = 0.0;
-  if (P.kind == 1) e = sqrt(tot);
-  else if (P.kind == 2) e = (double)P.alpha * sqrt(tot) + (double)P.beta;
-  *job.e_out = (float)e;
-  // strictly exceeding T selects h; +inf pins l, -inf pins h; no estimator: always l
-  *job.k_out = (P.kind != 0 && e > (double)P.T) ? P.h : P.l;
-}
-
-// LDS of a selector workgroup
+// LDS of a selector workgroup / of the finishing step
 struct SelShared {
   double sq[kSelMaxRank];
-  uint32_t is_last;
 };
 
-// The group part: the decision of every member of the group whose estimator is "none" or the linear regression;
-// sum x^2 is added up once, when a member asks for it.  The member's parameters come from `params` (row of the
-// active target), or, for a lone job, from `one`.
+// What the finishing step needs of a selector job (a copy of it travels in the GEMV job record)
+struct SelFinish {
+  const double* ws;
+  float* e_out;
+  int32_t* k_out;
+  int32_t in, linear, nchunks, ws_rows;
+};
+__host__ __device__ inline SelFinish sel_finish_of(const SelJob& j) {
+  return SelFinish{j.ws, j.e_out, j.k_out, j.in, j.linear, j.nchunks, j.ws_rows};
+}
+
+// The estimate from what the selector launch left in the workspace, and the decision; called by all `nthreads`
+// threads of a workgroup (it holds workgroup barriers), every thread returns the bitwidth.  write: thread 0 also
+// stores the estimate and the bitwidth.  The partial products were written by an earlier launch.
+__device__ __forceinline__ int selector_finish(const SelFinish& f, const SelParams& P, int tid, int nthreads, double* sq, bool write) {
+  const DPLLM_SEL_GLOBAL double* ws = (const DPLLM_SEL_GLOBAL double*)f.ws;
+  double e = 0.0;
+  if (P.kind == 1) {
+    for (int t = tid; t < P.r; t += nthreads) {
+      double g = 0.0;
+      for (int c = 0; c < f.nchunks; ++c) g += ws[(size_t)c * f.ws_rows + t];
+      sq[t] = g * g;
+    }
+    __syncthreads();
+    double tot = 0.0;
+    for (int t = 0; t < P.r; ++t) tot += sq[t];   // the same sum in every thread
+    __syncthreads();                              // sq may be reused by the caller
+    e = sqrt(tot);
+  } else if (P.kind == 2) {
+    e = (double)P.alpha * sqrt(ws[0]) + (double)P.beta;
+  }
+  // strictly exceeding T selects h; +inf pins l, -inf pins h; no estimator: always l
+  const int k = (P.kind != 0 && e > (double)P.T) ? P.h : P.l;
+  if (write && tid == 0) {
+    *f.e_out = (float)e;
+    *f.k_out = k;
+  }
+  return k;
+}
+
+// The group part: sum x^2, added up once for the jobs of the launch that read the same vector and left in the
+// slot of every member whose estimator under the active target is the linear regression.
 __device__ __forceinline__ void selector_group_part(const SelJob* jobs, int first, const SelParams* params, const SelJob& lone,
                                                     const SelParams& one, int tid, SelShared& sh) {
   const int wave = tid >> 6, lane = tid & 63;
@@ -147,43 +174,38 @@ __device__ __forceinline__ void selector_group_part(const SelJob* jobs, int firs
   } else {
     need = one.kind == 2;
   }
-  double tot = 0.0;
-  if (need) {   // wavefront-uniform
-    double acc = 0.0;
-    for (int c = tid * 8; c < head.in; c += kSelPartThreads * 8) {
-      const sel_u32x4 xv = *(const DPLLM_SEL_GLOBAL sel_u32x4*)(head.x + c);
-      const __half* xh = reinterpret_cast<const __half*>(&xv);
+  if (!need) return;   // workgroup-uniform
+  double acc = 0.0;
+  for (int c = tid * 8; c < head.in; c += kSelPartThreads * 8) {
+    const sel_u32x4 xv = *(const DPLLM_SEL_GLOBAL sel_u32x4*)(head.x + c);
+    const __half* xh = reinterpret_cast<const __half*>(&xv);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float v = __half2float(xh[i]);
-        acc += (double)(v * v);  // exact square in fp32
-      }
+    for (int i = 0; i < 8; ++i) {
+      float v = __half2float(xh[i]);
+      acc += (double)(v * v);  // exact square in fp32
     }
-    acc = wave_sum_f64(acc);
-    if (lane == 0) sh.sq[wave] = acc;
-    __syncthreads();
-    for (int w = 0; w < kSelPartWaves; ++w) tot += sh.sq[w];
   }
+  acc = wave_sum_f64(acc);
+  if (lane == 0) sh.sq[wave] = acc;
+  __syncthreads();
   if (tid != 0) return;
+  double tot = 0.0;
+  for (int w = 0; w < kSelPartWaves; ++w) tot += sh.sq[w];
   if (jobs) {
-    for (int j = first; j >= 0; j = jobs[j].next) {
-      const SelParams P = params[jobs[j].linear];
-      if (P.kind != 1) selector_decide(jobs[j], P, tot);
-    }
-  } else if (one.kind != 1) {
-    selector_decide(lone, one, tot);
+    for (int j = first; j >= 0; j = jobs[j].next)
+      if (params[jobs[j].linear].kind == 2) jobs[j].ws[0] = tot;
+  } else {
+    lone.ws[0] = tot;
   }
 }
 
 // One projection part: wavefront w owns rows 16 rg + 4 w .. + 3 (clamped to r - 1; surplus rows are dropped),
 // columns [cb, ce) of them
-__device__ __forceinline__ void selector_proj_part(const SelJob& job, const SelParams& P, int part, int tid, SelShared& sh) {
+__device__ __forceinline__ void selector_proj_part(const SelJob& job, const SelParams& P, int part, int tid) {
   const int wave = tid >> 6, lane = tid & 63;
   if (P.kind != 1) return;                                    // this target estimates the linear otherwise
   const int rg = part / job.nchunks, ch = part - rg * job.nchunks;
-  const int rowgroups = sel_rowgroups_of(1, P.r);
-  if (rg >= rowgroups) return;                                // the pair of this target has fewer rows of G
-  const int nparts = rowgroups * job.nchunks;
+  if (rg >= sel_rowgroups_of(1, P.r)) return;                 // the pair of this target has fewer rows of G
   const int cb = ch * job.chunk_cols, ce = min(job.in, cb + job.chunk_cols);
   const int row0 = rg * kSelPartRows + wave * kSelRowsPerWave;
   const uint16_t* rows[kSelRowsPerWave];
@@ -216,48 +238,23 @@ __device__ __forceinline__ void selector_proj_part(const SelJob& job, const SelP
     }
   }
   DPLLM_SEL_GLOBAL double* ws = (DPLLM_SEL_GLOBAL double*)job.ws;
-  DPLLM_SEL_GLOBAL uint32_t* ticket = (DPLLM_SEL_GLOBAL uint32_t*)job.ticket;
 #pragma unroll
   for (int i = 0; i < kSelRowsPerWave; ++i) {
     const double rowsum = wave_sum_f64(acc[i]);
     if (lane == 0) ws[(size_t)ch * job.ws_rows + row0 + i] = rowsum;
   }
-  __syncthreads();   // the four wavefronts' stores happen before thread 0's fence
-  if (tid == 0) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const bool mine = old == (uint32_t)(nparts - 1);
-    if (mine) {
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-      __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // nobody else arrives in this launch
-    }
-    sh.is_last = mine;
-  }
-  __syncthreads();
-  if (!sh.is_last) return;
-  for (int t = tid; t < P.r; t += kSelPartThreads) {
-    double g = 0.0;
-    for (int c = 0; c < job.nchunks; ++c) g += ws[(size_t)c * job.ws_rows + t];
-    sh.sq[t] = g * g;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    double tot = 0.0;
-    for (int t = 0; t < P.r; ++t) tot += sh.sq[t];
-    selector_decide(job, P, tot);
-  }
 }
 
 // parts == nullptr: the single job `one_job` with the parameters `one`; workgroup b is its projection part b, or
-// (kinds "none" and "linear regression": one workgroup) its group part.  Else workgroup b serves parts[b] of the
-// launch's job table under the target *target.
+// (linear regression: one workgroup) its group part.  Else workgroup b serves parts[b] of the launch's job table
+// under the target *target.
 __global__ void __launch_bounds__(kSelPartThreads) selector_part_kernel(const SelJob* __restrict__ jobs, const SelPart* __restrict__ parts,
                                                                          const SelParams* __restrict__ params,
                                                                          const int32_t* __restrict__ target, int n_linears,
                                                                          SelJob one_job, SelParams one) {
   __shared__ SelShared sh;
   if (parts == nullptr) {
-    if (one.kind == 1) selector_proj_part(one_job, one, blockIdx.x, threadIdx.x, sh);
+    if (one.kind == 1) selector_proj_part(one_job, one, blockIdx.x, threadIdx.x);
     else selector_group_part(nullptr, 0, nullptr, one_job, one, threadIdx.x, sh);
     return;
   }
@@ -267,9 +264,25 @@ __global__ void __launch_bounds__(kSelPartThreads) selector_part_kernel(const Se
     selector_group_part(jobs, p.job, row, one_job, one, threadIdx.x, sh);
   } else {
     const SelJob job = jobs[p.job];
-    const SelParams P = row[job.linear];
-    selector_proj_part(job, P, p.part, threadIdx.x, sh);
+    selector_proj_part(job, row[job.linear], p.part, threadIdx.x);
   }
+}
+
+// The estimates and decisions of a selector launch, where no GEMV launch follows that takes them itself:
+// workgroup b finishes jobs[b] under the target *target (jobs == nullptr: the single job `one_job` with the
+// parameters `one`).  Launched after selector_part_kernel on the same stream.
+constexpr int kSelDecideThreads = 128;
+__global__ void __launch_bounds__(kSelDecideThreads) selector_decide_kernel(const SelJob* __restrict__ jobs, const SelParams* __restrict__ params,
+                                                                            const int32_t* __restrict__ target, int n_linears,
+                                                                            SelJob one_job, SelParams one) {
+  __shared__ SelShared sh;
+  if (jobs == nullptr) {
+    selector_finish(sel_finish_of(one_job), one, threadIdx.x, kSelDecideThreads, sh.sq, true);
+    return;
+  }
+  const SelJob job = jobs[blockIdx.x];
+  const SelParams P = params[(size_t)(*target) * n_linears + job.linear];
+  selector_finish(sel_finish_of(job), P, threadIdx.x, kSelDecideThreads, sh.sq, true);
 }
 
 }  // namespace dpllm
