@@ -154,6 +154,16 @@ int dpllm_set_selector_input(dpllm_model* m, int id, const void* xsel_dev);
 int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, float* e_dev,
                    int32_t* k_dev, void* stream);
 
+/* dpllm_estimate for callers that cannot allocate or hand over a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same result bit for bit, but the partial
+ * products of the selector travel through a fixed array in the library's own device image (64 KiB per GPU, held
+ * until the process ends) instead of the model's workspace.  It allocates nothing, needs no workspace, and
+ * enqueues two kernels on `stream`.  Limit: projection rank r <= 256 (ERANGE beyond).  All calls on one GPU, from
+ * any model or stream, share the array: calls that overlap in time on one GPU race, calls that follow one another
+ * on one stream do not.  Errors: EINVAL, ERANGE, ESTATE (pair not set), EHIP. */
+int dpllm_estimate_noalloc(dpllm_model* m, int id, int l, int h, const void* x_dev, float* e_dev,
+                           int32_t* k_dev, void* stream);
+
 /* "Run the GEMV at bitwidth k": y[b][o] = sum_c LUT_k[o][code_k(o,c)] * x[b][c], fp32
  * accumulation, fp16 result.  k >= 0: that bitwidth.  k < 0: the bitwidth is read on the
  * device from k_dev[0] (the hand-over from dpllm_estimate without a host round trip); a

@@ -22,7 +22,7 @@ SYMBOLS = ["dpllm_model_create", "dpllm_model_destroy", "dpllm_last_error", "dpl
            "dpllm_workspace_bytes", "dpllm_set_workspace",
            "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair",
            "dpllm_set_target_entry", "dpllm_set_target", "dpllm_set_selector_input",
-           "dpllm_estimate", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_copy", "dpllm_debug_read"]
+           "dpllm_estimate", "dpllm_estimate_noalloc", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_copy", "dpllm_debug_read"]
 
 
 class DpllmError(RuntimeError):
@@ -53,6 +53,7 @@ def _load():
     L.dpllm_set_target_entry.argtypes = [vp, i32, i32, i32, i32, f32]
     L.dpllm_set_target.argtypes = [vp, i32, vp]
     L.dpllm_estimate.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
+    L.dpllm_estimate_noalloc.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
     L.dpllm_gemv.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp]
     L.dpllm_decode_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
     L.dpllm_decode_step_parts.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp, i32, vp]
@@ -208,6 +209,11 @@ class Model:
         k_out = torch.empty(1, dtype=torch.int32, device="cuda") if k_out is None else k_out
         self._need_workspace()
         _check(self.h, lib.dpllm_estimate(self.h, id, l, h, _ptr(x), _ptr(e_out), _ptr(k_out), _stream()))
+        return e_out, k_out
+
+    def dpllm_estimate_noalloc(self, id, l, h, x, e_out, k_out):
+        """The variant that allocates nothing: the caller passes every buffer, no workspace is touched."""
+        _check(self.h, lib.dpllm_estimate_noalloc(self.h, id, l, h, _ptr(x), _ptr(e_out), _ptr(k_out), _stream()))
         return e_out, k_out
 
     def dpllm_gemv(self, id, k, x, y=None, k_dev=None):

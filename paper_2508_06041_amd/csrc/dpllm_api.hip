@@ -20,6 +20,14 @@
 
 using namespace dpllm;
 
+// Scratch of dpllm_estimate_noalloc: the partial dot products of one projection selector (rank up to
+// kStaticMaxRank, every column chunking) or its sum x^2.  Every GPU the library runs on holds its own copy of the
+// array until the process ends.  In host code the name is only a stand-in: the device address comes from
+// hipGetSymbolAddress, once per device (static_scratch_ptr), and only that pointer is handed to kernels.
+constexpr int kStaticMaxRank = 256;
+constexpr size_t kStaticScratchSlots = (size_t)kSelMaxChunks * kStaticMaxRank;
+static __device__ __align__(256) double scratch[kStaticScratchSlots];
+
 namespace {
 
 struct Pair {
@@ -541,6 +549,23 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   return DPLLM_OK;
 }
 
+// device address of `scratch` on the current device, looked up on the first call on that device
+constexpr int kMaxDevices = 64;
+int static_scratch_ptr(dpllm_model* m, double** out) {
+  static double* ptr[kMaxDevices] = {};
+  int dev = 0;
+  HIP_TRY(m, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(m, DPLLM_EINVAL, "device %d outside [0,%d)", dev, kMaxDevices);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(m, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(m, DPLLM_EHIP, "hipGetSymbolAddress returned a null address");
+    ptr[dev] = (double*)p;
+  }
+  *out = ptr[dev];
+  return DPLLM_OK;
+}
+
 bool capturing(hipStream_t st) {
   hipStreamCaptureStatus s = hipStreamCaptureStatusNone;
   if (hipStreamIsCapturing(st, &s) != hipSuccess) { (void)hipGetLastError(); return false; }
@@ -759,29 +784,60 @@ int dpllm_set_selector_input(dpllm_model* m, int id, const void* xsel_dev) {
   return DPLLM_OK;
 }
 
-int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, float* e_dev, int32_t* k_dev,
-                   void* stream) {
-  int rc = DPLLM_OK;
-  Linear* lin = get_linear(m, id, &rc);
-  if (!lin) return rc;
-  if (!x_dev || !e_dev || !k_dev) return fail(m, DPLLM_EINVAL, "null pointer");
-  if ((uintptr_t)x_dev % 16) return fail(m, DPLLM_EINVAL, "x not 16-byte aligned");
-  int slot = lin->find_pair(l, h);
-  if (slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
-  if (!m->ws.base) return fail(m, DPLLM_ESTATE, "no workspace set");
-  const Pair& sel = lin->sel[slot];
+// the two launches of a lone estimate: the parts leave their partial results in `slots`, the decide kernel finishes
+static int launch_estimate(dpllm_model* m, const Linear& lin, int id, const Pair& sel, const void* x_dev, float* e_dev, int32_t* k_dev,
+                           double* slots, hipStream_t st) {
   const int rowgroups = sel_rowgroups_of(sel.kind, sel.r);
-  SelJob j = make_sel_job(*lin, id, rowgroups, x_dev, e_dev, k_dev, rowgroups);
-  j.ws = m->ws.at<double>(m->ws.est_ws);
+  SelJob j = make_sel_job(lin, id, rowgroups, x_dev, e_dev, k_dev, rowgroups);
+  j.ws = slots;
   const SelParams P = make_params(sel, sel.T);
   const int blocks = sel.kind == DPLLM_SEL_PROJ ? rowgroups * j.nchunks : sel.kind == DPLLM_SEL_LINREG ? 1 : 0;
   if (blocks > 0)
-    hipLaunchKernelGGL(selector_part_kernel, dim3(blocks), dim3(kSelPartThreads), 0, (hipStream_t)stream, (const SelJob*)nullptr,
+    hipLaunchKernelGGL(selector_part_kernel, dim3(blocks), dim3(kSelPartThreads), 0, st, (const SelJob*)nullptr,
                        (const SelPart*)nullptr, (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, P);
-  hipLaunchKernelGGL(selector_decide_kernel, dim3(1), dim3(kSelDecideThreads), 0, (hipStream_t)stream, (const SelJob*)nullptr,
+  hipLaunchKernelGGL(selector_decide_kernel, dim3(1), dim3(kSelDecideThreads), 0, st, (const SelJob*)nullptr,
                      (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, P);
   HIP_TRY(m, hipGetLastError());
   return DPLLM_OK;
+}
+
+static int check_estimate_args(dpllm_model* m, int id, int l, int h, const void* x_dev, float* e_dev, int32_t* k_dev, Linear** lin,
+                               int* slot) {
+  int rc = DPLLM_OK;
+  *lin = get_linear(m, id, &rc);
+  if (!*lin) return rc;
+  if (!x_dev || !e_dev || !k_dev) return fail(m, DPLLM_EINVAL, "null pointer");
+  if ((uintptr_t)x_dev % 16) return fail(m, DPLLM_EINVAL, "x not 16-byte aligned");
+  *slot = (*lin)->find_pair(l, h);
+  if (*slot < 0) return fail(m, DPLLM_ESTATE, "pair (%d,%d) not set on linear %d", l, h, id);
+  return DPLLM_OK;
+}
+
+int dpllm_estimate(dpllm_model* m, int id, int l, int h, const void* x_dev, float* e_dev, int32_t* k_dev,
+                   void* stream) {
+  Linear* lin = nullptr;
+  int slot = -1;
+  int rc = check_estimate_args(m, id, l, h, x_dev, e_dev, k_dev, &lin, &slot);
+  if (rc != DPLLM_OK) return rc;
+  if (!m->ws.base) return fail(m, DPLLM_ESTATE, "no workspace set");
+  return launch_estimate(m, *lin, id, lin->sel[slot], x_dev, e_dev, k_dev, m->ws.at<double>(m->ws.est_ws), (hipStream_t)stream);
+}
+
+int dpllm_estimate_noalloc(dpllm_model* m, int id, int l, int h, const void* x_dev, float* e_dev, int32_t* k_dev,
+                           void* stream) {
+  Linear* lin = nullptr;
+  int slot = -1;
+  int rc = check_estimate_args(m, id, l, h, x_dev, e_dev, k_dev, &lin, &slot);
+  if (rc != DPLLM_OK) return rc;
+  const Pair& sel = lin->sel[slot];
+  if (sel.kind == DPLLM_SEL_PROJ && sel.r > kStaticMaxRank)
+    return fail(m, DPLLM_ERANGE, "rank %d beyond the static scratch (at most %d): use dpllm_estimate with a workspace", sel.r, kStaticMaxRank);
+  double* slots = nullptr;
+  rc = static_scratch_ptr(m, &slots);
+  if (rc != DPLLM_OK) return rc;
+  // nothing in the scratch has to start at zero: every slot the decide kernel reads is written by the parts of
+  // this call first (the previous call's contents are never read)
+  return launch_estimate(m, *lin, id, sel, x_dev, e_dev, k_dev, slots, (hipStream_t)stream);
 }
 
 int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* x_dev, void* y_dev, int B,
