@@ -84,6 +84,7 @@ struct Phase {
   int blocks = 0;                       // workgroups of that launch
   int block_first = 0;                  // slice of the device workgroup-to-job table
   std::vector<int> plain;               // linears served by the plain kernel, one launch each
+  bool estimators = true;               // under some target a job of the selector launch has an estimator (else the launch is skipped)
   bool decide = false;                  // a linear of the selector launch is served by the plain kernel, which reads its
                                         // bitwidth from k_dev: the decisions of this launch are taken by a launch of their own
 };
@@ -273,6 +274,7 @@ GemvJob make_gemv_job(const Linear& lin, int k, const int32_t* k_dev, const void
 // end of the launch (measured on the 7B step: 0.25 MiB 496 us, 0.375 MiB 480, 0.75 MiB 471, 1 MiB 468, 2 MiB
 // 477, 4 MiB 546); and a launch wants at least a few workgroups per compute unit.
 constexpr long kLaneGroupBytes = 1048576;
+constexpr int kLaneSplitBlocks = 256;   // a launch that splits columns aims at one workgroup per compute unit
 int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks, long group_bytes = kLaneGroupBytes) {
   const long bytes_per_block = 64L * L.in * k / 8;
   long r = std::min<long>(16, std::max<long>(1, group_bytes / std::max<long>(1, bytes_per_block)));
@@ -287,7 +289,7 @@ int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks, long 
 // workgroups = those of the whole launch before splitting; rows = blocks of rows x samples per pass x groups of
 // the job; pool = what is left of the partial-sum pool.
 int pick_lane_split(const LinearLayout& L, long workgroups, long rows, long pool) {
-  long s = std::min<long>(8, 320 / std::max<long>(1, workgroups));
+  long s = std::min<long>(8, kLaneSplitBlocks / std::max<long>(1, workgroups));
   s = std::min<long>(s, L.ncc / kLaneWaves);   // at least one tile per wavefront
   while (s > 1 && rows * s > pool) --s;
   return (int)std::max<long>(1, s);
@@ -373,6 +375,14 @@ void fill_params(dpllm_model* m) {
 
 int upload_params(dpllm_model* m, hipStream_t st) {
   fill_params(m);
+  // a selector launch none of whose linears has an estimator under any target has nothing to compute
+  const size_t n = m->linears.size();
+  for (Phase& ph : m->plan.phases) {
+    ph.estimators = false;
+    for (int j = ph.sel_first; j < ph.sel_first + ph.sel_count && !ph.estimators; ++j)
+      for (int t = 0; t < DPLLM_MAX_TARGETS && !ph.estimators; ++t)
+        ph.estimators = m->h_params[(size_t)t * n + m->h_sel_jobs[j].linear].kind != DPLLM_SEL_NONE;
+  }
   HIP_TRY(m, hipMemcpyAsync(m->ws.at<SelParams>(m->ws.sel_params), m->h_params.data(), sizeof(SelParams) * m->h_params.size(),
                             hipMemcpyHostToDevice, st));
   m->params_dirty = false;
@@ -546,6 +556,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     HIP_TRY(m, hipMemcpyAsync(W.at<GemvJob>(W.gemv_jobs), gemv_jobs.data(), sizeof(GemvJob) * gemv_jobs.size(), hipMemcpyHostToDevice, st));
   P.version = m->version;
   P.valid = true;
+  m->params_dirty = true;   // the phases' estimator flags are worked out with the parameter table
   return DPLLM_OK;
 }
 
@@ -896,8 +907,9 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
   for (const Phase& ph : P.phases) {
     if ((parts & DPLLM_STEP_SELECT) && ph.sel_count > 0) {
       const SelJob* jobs = W.at<SelJob>(W.sel_jobs) + ph.sel_first;
-      hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
-                         (const SelPart*)(W.at<SelPart>(W.sel_parts) + ph.part_first), d_params, d_target, n, none, pnone);
+      if (ph.estimators)
+        hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
+                           (const SelPart*)(W.at<SelPart>(W.sel_parts) + ph.part_first), d_params, d_target, n, none, pnone);
       // Whole step: the GEMV workgroups take the decisions of their linears themselves.  Selectors alone, or a
       // linear on the plain kernel: a launch that finishes every job of this selector launch.
       if (!both || ph.decide)

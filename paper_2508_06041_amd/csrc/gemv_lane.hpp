@@ -395,9 +395,12 @@ __device__ __forceinline__ void lane_group_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// tiles in registers per wavefront: one being decoded, one in flight (a third measured equal or up to 1.3 %
-// slower: with sixteen wavefronts on a compute unit the memory system has enough requests either way)
-template <int K, int NB>
+// Tiles in registers per wavefront: one being decoded, one in flight.  A third measured equal or up to 1.3 %
+// slower in launches that fill the chip (with sixteen wavefronts on a compute unit the memory system has enough
+// requests either way), and three or four tiles in flight did not help launches of a few hundred workgroups
+// either (one dependency level of a chained step: 9.2 -> 10.3 us for q, k, v of a 7B block): those are bound by
+// the chain launch -> job record -> selector results -> tables and first tiles -> decode, not by the number of
+// requests in flight.
 constexpr int kLaneDepth = 2;
 
 // One workgroup: row blocks block, block + step, ... of a job (step = nblocks / nsplit); it is number `split` of
@@ -408,7 +411,7 @@ constexpr int kLaneDepth = 2;
 template <int K, int NB>
 __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, int block, int split, int tid, char* lds) {
   constexpr int table_bytes = kLaneTableBytes;
-  constexpr int D = kLaneDepth<K, NB>;
+  constexpr int D = kLaneDepth;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const uint32_t lanecol = (uint32_t)lane * 4;  // the lane's column of the interleaved tables
   float* red = reinterpret_cast<float*>(lds + table_bytes);

@@ -119,7 +119,7 @@ __device__ __forceinline__ void sel_accumulate(const SelTile& t, bool valid, dou
 
 // LDS of a selector workgroup / of the finishing step
 struct SelShared {
-  double sq[kSelMaxRank];
+  double sq[kSelMaxRank + 1];   // [kSelMaxRank]: the total
 };
 
 // What the finishing step needs of a selector job (a copy of it travels in the GEMV job record)
@@ -134,22 +134,37 @@ __host__ __device__ inline SelFinish sel_finish_of(const SelJob& j) {
 }
 
 // The estimate from what the selector launch left in the workspace, and the decision; called by all `nthreads`
-// threads of a workgroup (it holds workgroup barriers), every thread returns the bitwidth.  write: thread 0 also
-// stores the estimate and the bitwidth.  The partial products were written by an earlier launch.
+// (a multiple of 64, at least 64) threads of a workgroup (it holds workgroup barriers), every thread returns the
+// bitwidth.  write: thread 0 also stores the estimate and the bitwidth.  The partial products were written by an
+// earlier launch.  Order of the additions (fixed, so that every workgroup that repeats them gets the same bits):
+// per row of G its chunks in chunk order; the squares of rows t, t + 64, t + 128, ... in that order in lane t of
+// the first wavefront; the 64 lane sums by a butterfly.  Loads are issued in batches ahead of the additions that
+// consume them: a workgroup of the GEMV kernel pays this latency before it can start streaming.
 __device__ __forceinline__ int selector_finish(const SelFinish& f, const SelParams& P, int tid, int nthreads, double* sq, bool write) {
   const DPLLM_SEL_GLOBAL double* ws = (const DPLLM_SEL_GLOBAL double*)f.ws;
   double e = 0.0;
   if (P.kind == 1) {
     for (int t = tid; t < P.r; t += nthreads) {
       double g = 0.0;
-      for (int c = 0; c < f.nchunks; ++c) g += ws[(size_t)c * f.ws_rows + t];
+      for (int c0 = 0; c0 < f.nchunks; c0 += 8) {
+        double v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = ws[(size_t)min(c0 + i, f.nchunks - 1) * f.ws_rows + t];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) g += c0 + i < f.nchunks ? v[i] : 0.0;
+      }
       sq[t] = g * g;
     }
     __syncthreads();
-    double tot = 0.0;
-    for (int t = 0; t < P.r; ++t) tot += sq[t];   // the same sum in every thread
+    if (tid < 64) {
+      double part = 0.0;
+      for (int t = tid; t < P.r; t += 64) part += sq[t];
+      part = wave_sum_f64(part);
+      if (tid == 0) sq[kSelMaxRank] = part;
+    }
+    __syncthreads();
+    e = sqrt(sq[kSelMaxRank]);
     __syncthreads();                              // sq may be reused by the caller
-    e = sqrt(tot);
   } else if (P.kind == 2) {
     e = (double)P.alpha * sqrt(ws[0]) + (double)P.beta;
   }
