@@ -468,7 +468,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       const Linear& lin = m->linears[j];
       const int rowgroups = lin.max_rowgroups();
       SelJob sj = make_sel_job(lin, j, rowgroups, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j, launch_rowgroups);
-      for (int part = 0; part < rowgroups * sj.nchunks; ++part) sel_parts.push_back(SelPart{(int)local, part});
+      for (int part = 0; part < rowgroups * sj.nchunks; ++part) sel_parts.push_back(SelPart{(int)local, part, j, 0});
       sj.ws = W.at<double>(W.sel_ws) + ws_slots;
       ws_slots += (size_t)sj.ws_rows * sj.nchunks;
       sel_job_of[j] = (int)sel_jobs.size();
@@ -487,7 +487,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
         const SelJob& jb = sel_jobs[ph.sel_first + b];
         if (jb.x == ja.x && jb.in == ja.in) { sel_jobs[ph.sel_first + prev].next = b; prev = b; }
       }
-      sel_parts.push_back(SelPart{a, -1});
+      sel_parts.push_back(SelPart{a, -1, ja.linear, 0});
     }
     ph.part_count = (int)sel_parts.size() - ph.part_first;
     // GEMV jobs of the phase: one launch of the streaming kernel for all linears it serves

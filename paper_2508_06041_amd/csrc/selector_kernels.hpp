@@ -69,8 +69,10 @@ struct SelJob {
   int32_t next;        // next job of the group that reads the same x in this launch (index in the launch's job table), -1: none
 };
 struct SelPart {
-  int32_t job;    // index into the job table of the launch
-  int32_t part;   // projection part number inside the job; -1: the group part of the group that starts at `job`
+  int32_t job;     // index into the job table of the launch
+  int32_t part;    // projection part number inside the job; -1: the group part of the group that starts at `job`
+  int32_t linear;  // the job's row in the parameter table (so that job record and parameters load side by side)
+  int32_t pad;
 };
 
 __host__ __device__ inline int sel_rowgroups_of(int kind, int r) {
@@ -263,7 +265,7 @@ __device__ __forceinline__ void selector_proj_part(const SelJob& job, const SelP
 // parts == nullptr: the single job `one_job` with the parameters `one`; workgroup b is its projection part b, or
 // (linear regression: one workgroup) its group part.  Else workgroup b serves parts[b] of the launch's job table
 // under the target *target.
-__global__ void __launch_bounds__(kSelPartThreads) selector_part_kernel(const SelJob* __restrict__ jobs, const SelPart* __restrict__ parts,
+__global__ void __launch_bounds__(kSelPartThreads) __attribute__((amdgpu_waves_per_eu(5))) selector_part_kernel(const SelJob* __restrict__ jobs, const SelPart* __restrict__ parts,
                                                                          const SelParams* __restrict__ params,
                                                                          const int32_t* __restrict__ target, int n_linears,
                                                                          SelJob one_job, SelParams one) {
@@ -278,8 +280,9 @@ __global__ void __launch_bounds__(kSelPartThreads) selector_part_kernel(const Se
   if (p.part < 0) {
     selector_group_part(jobs, p.job, row, one_job, one, threadIdx.x, sh);
   } else {
+    const SelParams P = row[p.linear];
     const SelJob job = jobs[p.job];
-    selector_proj_part(job, row[job.linear], p.part, threadIdx.x);
+    selector_proj_part(job, P, p.part, threadIdx.x);
   }
 }
 
