@@ -58,6 +58,9 @@ def main():
                     help="thresholds = this quantile of the calibration estimates (0.75: the 3.25-bit target) instead of tau-based ones")
     ap.add_argument("--hybrid", action="store_true",
                     help="every second linear takes the linear-regression estimator (Sec. 5.1: about half the layers)")
+    ap.add_argument("--pin-k", type=int, default=None,
+                    help="every layer pinned to this bitwidth for the whole run (no estimator: the paper's +/-inf protocol); "
+                         "used with --sections step for per-bitwidth counter profiles")
     ap.add_argument("--sections", default=",".join(ALL_SECTIONS), help="comma list of " + ", ".join(ALL_SECTIONS))
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only (no HIP graph replay)")
     ap.add_argument("--copy-yardstick", action="store_true",
@@ -154,6 +157,12 @@ def main():
             reps += 1
         return total / (reps * steps), reps
 
+    if args.pin_k is not None:
+        for i in range(n):
+            model.dpllm_set_selector(i, args.pin_k, args.pin_k, dp.DPLLM_SEL_NONE)
+        l = h = args.pin_k
+        for s_ in sel:
+            s_["kind"] = 0
     out = {}
     # ---- the decode step under thresholds (selectors + GEMVs), all linears one group -------------------------
     def full_step(t):
@@ -397,7 +406,9 @@ def main():
         "config": {"workload": "Llama-%s-shaped decode step: %d blocks x 7 linears, p=%d bitplanes, (l,h)=(3,4), "
                                "rank-64 projection selectors%s, thresholds %s, %d outlier-fp16 activation vectors, batch 1, "
                                "all linears of the step in one dependency group"
-                               % (args.model.upper(), args.blocks, p, " (every second linear: linear regression)" if args.hybrid else "",
+                               % (args.model.upper(), args.blocks, p,
+                                  (" (every second linear: linear regression)" if args.hybrid else "") +
+                                  (" REPLACED by every layer pinned to k=%d" % args.pin_k if args.pin_k is not None else ""),
                                   "tau~U[0.05,0.3] x median||W_h x||" if args.quantile is None else "= %.2f-quantile of the calibration estimates" % args.quantile,
                                   n_x),
                    "linears": n, "frac_of_hbm_peak": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),

@@ -63,6 +63,27 @@ __device__ __forceinline__ uint32_t bfi_insn(uint32_t mask, uint32_t a, uint32_t
   return r;
 }
 
+// (a & m) | (b & ~m) with all three operands in vector registers: v_bitop3_b32 runs at full rate (a wavefront
+// instruction every two cycles per SIMD) only in that form; with a scalar or literal operand, and v_bfi_b32 /
+// v_and_or_b32 in any form, take four cycles (measured).  The masks of the merge trees are therefore kept in
+// vector registers (vreg_const, once per workgroup).
+__device__ __forceinline__ uint32_t bfi_v(uint32_t m, uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0xca" : "=v"(r) : "v"(m), "v"(a), "v"(b));
+  return r;
+}
+// (a & m) | b, same form
+__device__ __forceinline__ uint32_t and_or_v(uint32_t a, uint32_t m, uint32_t b) {
+  uint32_t r;
+  asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0xea" : "=v"(r) : "v"(a), "v"(m), "v"(b));
+  return r;
+}
+__device__ __forceinline__ uint32_t vreg_const(uint32_t c) {
+  uint32_t r;
+  asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "s"(c));
+  return r;
+}
+
 // Pointers read from a job record are generic; the kernels turn them into global-address-space pointers so
 // that loads use the vector-memory counter only and do not tie up the LDS counter the lookups wait on.
 #define DPLLM_GLOBAL __attribute__((address_space(1)))
@@ -119,6 +140,80 @@ __device__ __forceinline__ void merge_nibble_pairs(const uint32_t (&w)[4], uint3
   T[1] = __builtin_rotateright32(bfi(field_mask(4, 1, 2), A[0][1], A[1][1]), 2);
   T[2] = __builtin_rotateright32(bfi(field_mask(4, 2, 2), A[0][0], A[1][0]), 3);
   T[3] = bfi(field_mask(4, 3, 2), A[0][1], A[1][1]);
+}
+
+// The same trees with their masks in vector registers (MergeMasks<K>::init, once per workgroup).
+template <int K>
+struct MergeMasks {
+  static constexpr int count = K == 3 ? 8 : K == 4 ? 6 : 15;   // k >= 5: 14 masks and a zero
+  uint32_t m[count];
+  __device__ __forceinline__ void init() {
+    if constexpr (K == 3) {
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        m[2 * jj] = vreg_const(rotl_c(0x90909090u, 2 * jj));
+        m[2 * jj + 1] = vreg_const(rotl_c(0x48484848u, 2 * jj));
+      }
+    } else {
+      m[0] = vreg_const(field_mask(2, 0, 1));
+      m[1] = vreg_const(field_mask(2, 1, 1));
+#pragma unroll
+      for (int c = 0; c < 4; ++c) m[2 + c] = vreg_const(field_mask(4, c, 2));
+      if constexpr (K >= 5) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) m[6 + c] = vreg_const(field_mask(8, c, 4));
+        m[14] = vreg_const(0u);
+      }
+    }
+  }
+};
+
+template <int K, int D>
+__device__ __forceinline__ void merge_byte_fields_v(const uint32_t (&w)[K], uint32_t (&R)[8], const MergeMasks<K>& M) {
+  constexpr int d = D;
+  const uint32_t zero = M.m[14];
+  uint32_t v[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) v[s] = (s >= d && s < d + K) ? w[(s >= d && s < d + K) ? s - d : 0] : zero;
+  uint32_t A[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (2 * i + 1 >= d && 2 * i < d + K) {   // at least one of the two slots holds a plane
+      A[i][0] = bfi_v(M.m[0], v[2 * i], v[2 * i + 1]);
+      A[i][1] = bfi_v(M.m[1], v[2 * i], v[2 * i + 1]);
+    } else {
+      A[i][0] = A[i][1] = zero;
+    }
+  }
+  uint32_t B[2][4];
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    B[g][0] = bfi_v(M.m[2], A[2 * g][0], A[2 * g + 1][0]);
+    B[g][1] = bfi_v(M.m[3], A[2 * g][1], A[2 * g + 1][1]);
+    B[g][2] = bfi_v(M.m[4], A[2 * g][0], A[2 * g + 1][0]);
+    B[g][3] = bfi_v(M.m[5], A[2 * g][1], A[2 * g + 1][1]);
+  }
+  R[0] = __builtin_rotateright32(bfi_v(M.m[6], B[0][0], B[1][0]), 1);
+  R[1] = __builtin_rotateright32(bfi_v(M.m[7], B[0][1], B[1][1]), 2);
+  R[2] = __builtin_rotateright32(bfi_v(M.m[8], B[0][2], B[1][2]), 3);
+  R[3] = __builtin_rotateright32(bfi_v(M.m[9], B[0][3], B[1][3]), 4);
+  R[4] = __builtin_rotateright32(bfi_v(M.m[10], B[0][0], B[1][0]), 5);
+  R[5] = __builtin_rotateright32(bfi_v(M.m[11], B[0][1], B[1][1]), 6);
+  R[6] = __builtin_rotateright32(bfi_v(M.m[12], B[0][2], B[1][2]), 7);
+  R[7] = bfi_v(M.m[13], B[0][3], B[1][3]);
+}
+
+__device__ __forceinline__ void merge_nibble_pairs_v(const uint32_t (&w)[4], uint32_t (&T)[4], const MergeMasks<4>& M) {
+  uint32_t A[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    A[i][0] = bfi_v(M.m[0], w[2 * i], w[2 * i + 1]);
+    A[i][1] = bfi_v(M.m[1], w[2 * i], w[2 * i + 1]);
+  }
+  T[0] = __builtin_rotateright32(bfi_v(M.m[2], A[0][0], A[1][0]), 1);
+  T[1] = __builtin_rotateright32(bfi_v(M.m[3], A[0][1], A[1][1]), 2);
+  T[2] = __builtin_rotateright32(bfi_v(M.m[4], A[0][0], A[1][0]), 3);
+  T[3] = bfi_v(M.m[5], A[0][1], A[1][1]);
 }
 
 // columns of the two weights in byte m of word c of merge_nibble_pairs: upper nibble, lower nibble

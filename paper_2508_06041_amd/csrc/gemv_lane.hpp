@@ -159,11 +159,10 @@ __device__ __forceinline__ void lane_park_x(uint32_t x, int lane, char* scratch,
 // ---- entry words of one 32-column word -----------------------------------------------------------------------
 // k = 3: four words of four bytes (8 a + b) + 64 (two bits of other weights, cleared when the address is formed),
 // the pairs (2i, 2i+1), i = 4 jj + n (word 3 is left rotated by one byte: its pair n sits in byte n + 1)
-__device__ __forceinline__ void lane_entries3(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t (&T)[4]) {
+__device__ __forceinline__ void lane_entries3(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t (&T)[4], const MergeMasks<3>& M) {
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj) {
-    const uint32_t m0 = rotl_c(0x90909090u, 2 * jj), m1 = rotl_c(0x48484848u, 2 * jj);
-    const uint32_t o = bfi_insn(m0, w0, bfi_insn(m1, w1, w2));
+    const uint32_t o = bfi_v(M.m[2 * jj], w0, bfi_v(M.m[2 * jj + 1], w1, w2));
     T[jj] = jj == 3 ? o : __builtin_rotateright32(o, 2 * jj + 2);   // jj = 3: a whole byte, taken care of by the byte index
   }
 }
@@ -235,12 +234,20 @@ __device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], con
   dot2_quad<JJ>(acc[0], x.x, v[0] | (v[1] << 16));
 }
 
+// k = 5, 6: the merge tree with its masks in vector registers (full-rate instructions); k = 7, 8 have no registers
+// to spare for fifteen masks at two workgroups per compute unit and keep them in the instructions
+template <int K>
+__device__ __forceinline__ void lane_merge_fields(const uint32_t (&w)[K], uint32_t (&R)[8], const MergeMasks<K>& M) {
+  if constexpr (K <= 6) merge_byte_fields_v<K, LaneDecode<K>::d>(w, R, M);
+  else merge_byte_fields<K, LaneDecode<K>::d>(w, R);
+}
+
 // ---- one tile -------------------------------------------------------------------------------------------------
 // Lookups run in chunks of eight; the next chunk's lookups are issued before the current chunk's multiply-adds.
 // xready: the parked activations of sample 0; sample b at + b * xstep
 template <int K, int NB>
 __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t lanecol, int lane, const char* lds, const char* xready,
-                                             int xstep, float (&acc)[NB][4], uint32_t (&addr)[8], uint32_t mask) {
+                                             int xstep, float (&acc)[NB][4], uint32_t (&addr)[8], uint32_t mask, const MergeMasks<K>& M) {
   uint32_t va[8], vb[8];
   u32x4 xq[NB][4];   // xq[b][j][m] = pair 4 q + m of word j of sample b, q = lane mod 4
 #pragma unroll
@@ -252,10 +259,10 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t 
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if constexpr (K == 3) {
-        lane_entries3(t.w[0][j], t.w[1][j], t.w[2][j], T[j]);
+        lane_entries3(t.w[0][j], t.w[1][j], t.w[2][j], T[j], M);
       } else {
         const uint32_t w[4] = {t.w[0][j], t.w[1][j], t.w[2][j], t.w[3][j]};
-        merge_nibble_pairs(w, T[j]);
+        merge_nibble_pairs_v(w, T[j], M);
       }
     }
     lane_issue_pairs<0, K == 3>(T[0], lanecol, lds, va, addr, mask);
@@ -282,7 +289,7 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t 
       uint32_t w[K];
 #pragma unroll
       for (int b = 0; b < K; ++b) w[b] = t.w[b][0];
-      merge_byte_fields<K, LaneDecode<K>::d>(w, R[0]);
+      lane_merge_fields<K>(w, R[0], M);
     }
     lane_issue_singles<K, 0>(R[0], lanecol, lds, va);
 #pragma unroll
@@ -291,7 +298,7 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t 
         uint32_t w[K];
 #pragma unroll
         for (int b = 0; b < K; ++b) w[b] = t.w[b][(j + 1) & 3];
-        merge_byte_fields<K, LaneDecode<K>::d>(w, R[(j + 1) & 1]);
+        lane_merge_fields<K>(w, R[(j + 1) & 1], M);
       }
       lane_issue_singles<K, 1>(R[j & 1], lanecol, lds, vb);
       sched_fence();
@@ -467,6 +474,8 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   float acc[NB][4];
 #pragma unroll
   for (int b = 0; b < NB; ++b) acc[b][0] = acc[b][1] = acc[b][2] = acc[b][3] = 0.f;
+  MergeMasks<K> M;
+  if constexpr (K <= 6) M.init();
   uint32_t addr[8], mask = 0x3fu;              // k = 3: address registers of the lookups (see lane_issue_pairs)
 #pragma unroll
   for (int i = 0; i < 8; ++i) addr[i] = lanecol;
@@ -547,7 +556,7 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
         for (int b = 0; b < NB; ++b) lane_park_x<K>(lane_mask_x(job, cc, lane, ring[s].x[b]), lane, slot + b * 512, slot + b * 512 + 256);
         xready = slot + 256;
       }
-      lane_compute<K, NB>(ring[s], lanecol, lane, lds, xready, 512, acc, addr, mask);
+      lane_compute<K, NB>(ring[s], lanecol, lane, lds, xready, 512, acc, addr, mask, M);
       if (++cc >= c1) {
         close_block();
         rb += step;
@@ -572,8 +581,8 @@ __device__ __forceinline__ void gemv_lane_block(const GemvJob& job, int block, i
   if (block >= job.nrq) return;
   int k = job.k;
   if (job.has_fin && params != nullptr) {
-    const SelParams P = params[(size_t)(*target) * n_linears + job.fin.linear];
-    k = selector_finish(job.fin, P, tid, kLaneThreads, reinterpret_cast<double*>(lds), first);   // the tables are not built yet
+    k = selector_finish(job.fin, params + (size_t)(*target) * n_linears + job.fin.linear, tid, kLaneThreads,
+                        reinterpret_cast<double*>(lds), first);   // the tables are not built yet
     k = __builtin_amdgcn_readfirstlane(k);
   } else if (job.k_dev != nullptr) {
     k = __builtin_amdgcn_readfirstlane(*as_global(job.k_dev));

@@ -142,16 +142,24 @@ __host__ __device__ inline SelFinish sel_finish_of(const SelJob& j) {
 // per row of G its chunks in chunk order; the squares of rows t, t + 64, t + 128, ... in that order in lane t of
 // the first wavefront; the 64 lane sums by a butterfly.  Loads are issued in batches ahead of the additions that
 // consume them: a workgroup of the GEMV kernel pays this latency before it can start streaming.
-__device__ __forceinline__ int selector_finish(const SelFinish& f, const SelParams& P, int tid, int nthreads, double* sq, bool write) {
+__device__ __forceinline__ int selector_finish(const SelFinish& f, const SelParams* prow, int tid, int nthreads, double* sq, bool write) {
   const DPLLM_SEL_GLOBAL double* ws = (const DPLLM_SEL_GLOBAL double*)f.ws;
+  // the first batch of partial products is asked for before the parameters, so that both arrive together (what
+  // the batch means is known once the parameters are here: slot 0 may also be sum x^2)
+  double v[8];
+  const int t0 = min(tid, f.ws_rows - 1);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = ws[(size_t)min(i, f.nchunks - 1) * f.ws_rows + t0];
+  const SelParams P = *prow;
   double e = 0.0;
   if (P.kind == 1) {
     for (int t = tid; t < P.r; t += nthreads) {
       double g = 0.0;
       for (int c0 = 0; c0 < f.nchunks; c0 += 8) {
-        double v[8];
+        if (c0 > 0 || t != tid) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = ws[(size_t)min(c0 + i, f.nchunks - 1) * f.ws_rows + t];
+          for (int i = 0; i < 8; ++i) v[i] = ws[(size_t)min(c0 + i, f.nchunks - 1) * f.ws_rows + t];
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) g += c0 + i < f.nchunks ? v[i] : 0.0;
       }
@@ -295,12 +303,11 @@ __global__ void __launch_bounds__(kSelDecideThreads) selector_decide_kernel(cons
                                                                             SelJob one_job, SelParams one) {
   __shared__ SelShared sh;
   if (jobs == nullptr) {
-    selector_finish(sel_finish_of(one_job), one, threadIdx.x, kSelDecideThreads, sh.sq, true);
+    selector_finish(sel_finish_of(one_job), &one, threadIdx.x, kSelDecideThreads, sh.sq, true);
     return;
   }
   const SelJob job = jobs[blockIdx.x];
-  const SelParams P = params[(size_t)(*target) * n_linears + job.linear];
-  selector_finish(sel_finish_of(job), P, threadIdx.x, kSelDecideThreads, sh.sq, true);
+  selector_finish(sel_finish_of(job), params + (size_t)(*target) * n_linears + job.linear, threadIdx.x, kSelDecideThreads, sh.sq, true);
 }
 
 }  // namespace dpllm
