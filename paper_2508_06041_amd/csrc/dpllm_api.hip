@@ -80,6 +80,7 @@ struct Linear {
 struct Phase {
   int sel_first = 0, sel_count = 0;     // slice of the device selector job table
   int part_first = 0, part_count = 0;   // slice of the device selector part table
+  int member_first = 0;                 // slice of the device table of group members
   int gemv_first = 0, gemv_count = 0;   // slice of the device GEMV job table (streaming kernel, one launch)
   int blocks = 0;                       // workgroups of that launch
   int block_first = 0;                  // slice of the device workgroup-to-job table
@@ -109,7 +110,7 @@ struct Workspace {
   size_t est_ws = 0;                         // dpllm_estimate: kSelOneSlots fp64
   size_t target = 0;                         // the number of the active target
   size_t sel_params = 0;                     // SelParams [DPLLM_MAX_TARGETS][n]
-  size_t sel_jobs = 0;                       // SelJob [n]
+  size_t sel_jobs = 0, sel_members = 0;      // SelJob [n], int32 [n]
   size_t sel_parts = 0, sel_parts_cap = 0;   // SelPart [cap]
   size_t sel_ws = 0, sel_ws_cap = 0;         // fp64 [cap]
   size_t gemv_jobs = 0;                      // GemvJob [n]
@@ -131,6 +132,7 @@ struct dpllm_model {
   // host copies of what the plan puts into the workspace (kept so that the asynchronous copies have a source)
   std::vector<SelJob> h_sel_jobs;
   std::vector<SelPart> h_sel_parts;
+  std::vector<int32_t> h_sel_members;
   std::vector<GemvJob> h_gemv_jobs;
   std::vector<int32_t> h_block_jobs;
   std::vector<SelParams> h_params;
@@ -196,6 +198,7 @@ Workspace carve_workspace(const dpllm_model* m) {
   w.target = take(sizeof(int32_t));
   w.sel_params = take(sizeof(SelParams) * DPLLM_MAX_TARGETS * n);
   w.sel_jobs = take(sizeof(SelJob) * n);
+  w.sel_members = take(sizeof(int32_t) * n);
   w.sel_parts_cap = parts;
   w.sel_parts = take(sizeof(SelPart) * parts);
   w.sel_ws_cap = slots;
@@ -232,7 +235,7 @@ SelJob make_sel_job(const Linear& lin, int linear, int rowgroups, const void* x,
   if (rowgroups > 0) {
     // long rows are cut as well, so that the parts of a launch are of similar size (7B step: 32.5 -> 30.7 us)
     constexpr long max_cols = 4096;
-    long want = std::min<long>(kSelMaxChunks, 512 / std::max<long>(1, launch_rowgroups));
+    long want = std::min<long>(kSelMaxChunks, 1152 / std::max<long>(1, launch_rowgroups));   // 1280 parts run at once
     want = std::max<long>(want, std::min<long>(kSelMaxChunks, (lin.L.in + max_cols - 1) / max_cols));
     if (want > 1) {
       j.chunk_cols = (int)((lin.L.in + want - 1) / want + kSelChunkStep - 1) / kSelChunkStep * kSelChunkStep;   // <= want chunks
@@ -240,7 +243,7 @@ SelJob make_sel_job(const Linear& lin, int linear, int rowgroups, const void* x,
     }
   }
   j.ws_rows = std::max(1, rowgroups) * kSelPartRows;
-  j.next = -1;
+  j.pad = 0;
   return j;
 }
 
@@ -401,6 +404,8 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   P.phases.clear();
   std::vector<SelJob>& sel_jobs = m->h_sel_jobs;
   std::vector<SelPart>& sel_parts = m->h_sel_parts;
+  std::vector<int32_t>& sel_members = m->h_sel_members;
+  sel_members.clear();
   std::vector<GemvJob>& gemv_jobs = m->h_gemv_jobs;
   std::vector<int32_t>& block_jobs = m->h_block_jobs;
   sel_jobs.clear(); sel_parts.clear(); gemv_jobs.clear(); block_jobs.clear();
@@ -468,26 +473,27 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       const Linear& lin = m->linears[j];
       const int rowgroups = lin.max_rowgroups();
       SelJob sj = make_sel_job(lin, j, rowgroups, lin.sel_input ? lin.sel_input : xs[j], e_dev + j, k_dev + j, launch_rowgroups);
-      for (int part = 0; part < rowgroups * sj.nchunks; ++part) sel_parts.push_back(SelPart{(int)local, part, j, 0});
+      for (int part = 0; part < rowgroups * sj.nchunks; ++part) sel_parts.push_back(SelPart{(int)local, part, j, 0, 0, 0});
       sj.ws = W.at<double>(W.sel_ws) + ws_slots;
       ws_slots += (size_t)sj.ws_rows * sj.nchunks;
       sel_job_of[j] = (int)sel_jobs.size();
       if (!lin.streaming()) ph.decide = true;
       sel_jobs.push_back(sj);
     }
-    // groups of jobs that read the same vector: one more part each, which takes the decisions that need no
-    // projection (and adds up x^2 once for the group when the linear regression asks for it)
+    // groups of jobs that read the same vector: one more part each, which adds up x^2 once for the members whose
+    // estimator is the linear regression
+    ph.member_first = (int)sel_members.size();
     for (int a = 0; a < ph.sel_count; ++a) {
-      SelJob& ja = sel_jobs[ph.sel_first + a];
+      const SelJob& ja = sel_jobs[ph.sel_first + a];
       bool head = true;
       for (int b = 0; b < a && head; ++b) head = sel_jobs[ph.sel_first + b].x != ja.x || sel_jobs[ph.sel_first + b].in != ja.in;
       if (!head) continue;
-      int prev = a;
-      for (int b = a + 1; b < ph.sel_count; ++b) {
+      const int first = (int)sel_members.size() - ph.member_first;
+      for (int b = a; b < ph.sel_count; ++b) {
         const SelJob& jb = sel_jobs[ph.sel_first + b];
-        if (jb.x == ja.x && jb.in == ja.in) { sel_jobs[ph.sel_first + prev].next = b; prev = b; }
+        if (jb.x == ja.x && jb.in == ja.in) sel_members.push_back(b);
       }
-      sel_parts.push_back(SelPart{a, -1, ja.linear, 0});
+      sel_parts.push_back(SelPart{a, -1, ja.linear, (int)sel_members.size() - ph.member_first - first, first, 0});
     }
     ph.part_count = (int)sel_parts.size() - ph.part_first;
     // GEMV jobs of the phase: one launch of the streaming kernel for all linears it serves
@@ -552,6 +558,7 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
   if (!block_jobs.empty())
     HIP_TRY(m, hipMemcpyAsync(W.at<int32_t>(W.block_jobs), block_jobs.data(), sizeof(int32_t) * block_jobs.size(), hipMemcpyHostToDevice, st));
   HIP_TRY(m, hipMemcpyAsync(W.at<SelJob>(W.sel_jobs), sel_jobs.data(), sizeof(SelJob) * sel_jobs.size(), hipMemcpyHostToDevice, st));
+  HIP_TRY(m, hipMemcpyAsync(W.at<int32_t>(W.sel_members), sel_members.data(), sizeof(int32_t) * sel_members.size(), hipMemcpyHostToDevice, st));
   if (!gemv_jobs.empty())
     HIP_TRY(m, hipMemcpyAsync(W.at<GemvJob>(W.gemv_jobs), gemv_jobs.data(), sizeof(GemvJob) * gemv_jobs.size(), hipMemcpyHostToDevice, st));
   P.version = m->version;
@@ -805,7 +812,7 @@ static int launch_estimate(dpllm_model* m, const Linear& lin, int id, const Pair
   const int blocks = sel.kind == DPLLM_SEL_PROJ ? rowgroups * j.nchunks : sel.kind == DPLLM_SEL_LINREG ? 1 : 0;
   if (blocks > 0)
     hipLaunchKernelGGL(selector_part_kernel, dim3(blocks), dim3(kSelPartThreads), 0, st, (const SelJob*)nullptr,
-                       (const SelPart*)nullptr, (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, P);
+                       (const SelPart*)nullptr, (const int32_t*)nullptr, (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, P);
   hipLaunchKernelGGL(selector_decide_kernel, dim3(1), dim3(kSelDecideThreads), 0, st, (const SelJob*)nullptr,
                      (const SelParams*)nullptr, (const int32_t*)nullptr, 0, j, P);
   HIP_TRY(m, hipGetLastError());
@@ -909,7 +916,8 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
       const SelJob* jobs = W.at<SelJob>(W.sel_jobs) + ph.sel_first;
       if (ph.estimators)
         hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
-                           (const SelPart*)(W.at<SelPart>(W.sel_parts) + ph.part_first), d_params, d_target, n, none, pnone);
+                           (const SelPart*)(W.at<SelPart>(W.sel_parts) + ph.part_first),
+                           (const int32_t*)(W.at<int32_t>(W.sel_members) + ph.member_first), d_params, d_target, n, none, pnone);
       // Whole step: the GEMV workgroups take the decisions of their linears themselves.  Selectors alone, or a
       // linear on the plain kernel: a launch that finishes every job of this selector launch.
       if (!both || ph.decide)

@@ -42,7 +42,7 @@ namespace dpllm {
 constexpr int kSelPartThreads = 256;
 constexpr int kSelPartWaves = kSelPartThreads / 64;
 constexpr int kSelRowsPerWave = 4;   // rows of G a wavefront carries at once (they share the activation loads)
-constexpr int kSelDepth = 2;         // column tiles in registers: one being accumulated, one in flight
+constexpr int kSelDepth = 2;         // column tiles in registers: one being accumulated, one in flight (two in flight measured slower: 32 against 28 us for the 224 selectors of a 7B step)
 constexpr int kSelPartRows = kSelPartWaves * kSelRowsPerWave;
 constexpr int kSelMaxRank = 1024;
 constexpr int kSelMaxChunks = 32;    // column chunks of a job
@@ -66,12 +66,14 @@ struct SelJob {
   int32_t linear;      // row of the job's linear in the parameter table
   int32_t nchunks, chunk_cols;  // projection part p covers rows [16 (p / nchunks), + 16), columns [chunk_cols (p % nchunks), + chunk_cols)
   int32_t ws_rows;     // rows of one chunk's slots in ws (the largest rank of the linear's pairs, rounded up to 16)
-  int32_t next;        // next job of the group that reads the same x in this launch (index in the launch's job table), -1: none
+  int32_t pad;
 };
 struct SelPart {
   int32_t job;     // index into the job table of the launch
-  int32_t part;    // projection part number inside the job; -1: the group part of the group that starts at `job`
+  int32_t part;    // projection part number inside the job; -1: the group part of the group whose first member is `job`
   int32_t linear;  // the job's row in the parameter table (so that job record and parameters load side by side)
+  int32_t count;   // group part: members of the group; they are members[first .. first + count) of the launch's member
+  int32_t first;   //   table (indices into the job table), all reading the same vector
   int32_t pad;
 };
 
@@ -189,17 +191,17 @@ __device__ __forceinline__ int selector_finish(const SelFinish& f, const SelPara
 
 // The group part: sum x^2, added up once for the jobs of the launch that read the same vector and left in the
 // slot of every member whose estimator under the active target is the linear regression.
-__device__ __forceinline__ void selector_group_part(const SelJob* jobs, int first, const SelParams* params, const SelJob& lone,
-                                                    const SelParams& one, int tid, SelShared& sh) {
+__device__ __forceinline__ void selector_group_part(const SelJob* jobs, const int32_t* members, int count, const SelParams* params,
+                                                    const SelJob& lone, const SelParams& one, int tid, SelShared& sh) {
   const int wave = tid >> 6, lane = tid & 63;
-  const SelJob& head = jobs ? jobs[first] : lone;
-  bool need = false;
+  const SelJob& head = jobs ? jobs[members[0]] : lone;
+  int need = 0;
   if (jobs) {
-    for (int j = first; j >= 0; j = jobs[j].next) need = need || params[jobs[j].linear].kind == 2;
+    for (int i = tid; i < count; i += kSelPartThreads) need |= params[jobs[members[i]].linear].kind == 2;
   } else {
     need = one.kind == 2;
   }
-  if (!need) return;   // workgroup-uniform
+  if (!__syncthreads_or(need)) return;
   double acc = 0.0;
   for (int c = tid * 8; c < head.in; c += kSelPartThreads * 8) {
     const sel_u32x4 xv = *(const DPLLM_SEL_GLOBAL sel_u32x4*)(head.x + c);
@@ -213,13 +215,14 @@ __device__ __forceinline__ void selector_group_part(const SelJob* jobs, int firs
   acc = wave_sum_f64(acc);
   if (lane == 0) sh.sq[wave] = acc;
   __syncthreads();
-  if (tid != 0) return;
   double tot = 0.0;
   for (int w = 0; w < kSelPartWaves; ++w) tot += sh.sq[w];
   if (jobs) {
-    for (int j = first; j >= 0; j = jobs[j].next)
-      if (params[jobs[j].linear].kind == 2) jobs[j].ws[0] = tot;
-  } else {
+    for (int i = tid; i < count; i += kSelPartThreads) {
+      const SelJob& j = jobs[members[i]];
+      if (params[j.linear].kind == 2) j.ws[0] = tot;
+    }
+  } else if (tid == 0) {
     lone.ws[0] = tot;
   }
 }
@@ -272,21 +275,22 @@ __device__ __forceinline__ void selector_proj_part(const SelJob& job, const SelP
 
 // parts == nullptr: the single job `one_job` with the parameters `one`; workgroup b is its projection part b, or
 // (linear regression: one workgroup) its group part.  Else workgroup b serves parts[b] of the launch's job table
-// under the target *target.
+// under the target *target (members: the launch's table of group members).
 __global__ void __launch_bounds__(kSelPartThreads) __attribute__((amdgpu_waves_per_eu(5))) selector_part_kernel(const SelJob* __restrict__ jobs, const SelPart* __restrict__ parts,
+                                                                         const int32_t* __restrict__ members,
                                                                          const SelParams* __restrict__ params,
                                                                          const int32_t* __restrict__ target, int n_linears,
                                                                          SelJob one_job, SelParams one) {
   __shared__ SelShared sh;
   if (parts == nullptr) {
     if (one.kind == 1) selector_proj_part(one_job, one, blockIdx.x, threadIdx.x);
-    else selector_group_part(nullptr, 0, nullptr, one_job, one, threadIdx.x, sh);
+    else selector_group_part(nullptr, nullptr, 1, nullptr, one_job, one, threadIdx.x, sh);
     return;
   }
   const SelPart p = parts[blockIdx.x];
   const SelParams* row = params + (size_t)(*target) * n_linears;
   if (p.part < 0) {
-    selector_group_part(jobs, p.job, row, one_job, one, threadIdx.x, sh);
+    selector_group_part(jobs, members + p.first, p.count, row, one_job, one, threadIdx.x, sh);
   } else {
     const SelParams P = row[p.linear];
     const SelJob job = jobs[p.job];
