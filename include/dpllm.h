@@ -71,7 +71,7 @@ typedef struct dpllm_model dpllm_model; /* opaque host object */
  * HIP device.  *out receives the handle.  Errors: EINVAL, EHIP. */
 int dpllm_model_create(dpllm_model** out, int n_linears);
 
-/* Frees the handle and the library's workspace.  Caller-owned device memory is not
+/* Frees the handle.  Caller-owned device memory (arenas, G, the workspace) is not
  * touched.  NULL is accepted. */
 void dpllm_model_destroy(dpllm_model* m);
 

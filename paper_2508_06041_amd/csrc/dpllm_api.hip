@@ -502,11 +502,25 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
     long total_rq = 0, lane_groups = 0;
     for (int j = id; j < end; ++j)
       if (m->linears[j].streaming()) total_rq += m->linears[j].L.nrq;
-    for (int j = id; j < end; ++j) {
-      const Linear& lin = m->linears[j];
-      if (!lin.streaming()) continue;
-      const int rpb = pick_blocks_per_group(lin.L, lin.part_k(), total_rq);
-      lane_groups += (lin.L.nrq + rpb - 1) / rpb;
+    // The chip runs 512 workgroups at a time.  A launch of a few such rounds loses the unfilled part of its last
+    // round (2.7 rounds cost 3): the work per workgroup is scaled, between half and one and a half times the
+    // usual megabyte, to the value with the smallest estimate of rounds x (start-up + work of a workgroup).
+    long base_bytes = kLaneGroupBytes;
+    {
+      double best = 1e300;
+      for (int pct = 50; pct <= 150; pct += 5) {
+        const long gb = kLaneGroupBytes * pct / 100;
+        long groups = 0;
+        for (int j = id; j < end; ++j) {
+          const Linear& lin = m->linears[j];
+          if (!lin.streaming()) continue;
+          const int rpb = pick_blocks_per_group(lin.L, lin.part_k(), total_rq, gb);
+          groups += (lin.L.nrq + rpb - 1) / rpb;
+        }
+        const double rounds = std::ceil(groups / 512.0);
+        const double est = rounds * (4.0 + 85.0 * pct / 100) * (1.0 + 0.0005 * std::abs(pct - 100));   // ties: the usual size
+        if (est < best) { best = est; base_bytes = gb; lane_groups = groups; }
+      }
     }
     std::vector<long> bytes_after(end - id, 0);   // plane bytes of the launch that follow linear j
     {
@@ -529,8 +543,8 @@ int build_plan(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* 
       GemvJob gj = make_gemv_job(lin, 0, k_dev + j, xs[j], ys[j]);
       gj.has_fin = 1;
       gj.fin = sel_finish_of(sel_jobs[sel_job_of[j]]);
-      long group_bytes = kLaneGroupBytes;
-      if (taper && bytes_after[j - id] < 512 * kLaneGroupBytes) group_bytes /= 2;
+      long group_bytes = base_bytes;
+      if (taper && bytes_after[j - id] < 512 * base_bytes) group_bytes /= 2;
       const int rpb = pick_blocks_per_group(lin.L, lin.part_k(), total_rq, group_bytes);
       gj.nblocks = (lin.L.nrq + rpb - 1) / rpb;
       gj.nsplit = pick_lane_split(lin.L, lane_groups, lin.L.nrq, kLanePoolRows - pool_used);
