@@ -329,14 +329,14 @@ int launch_plain(dpllm_model* m, const Linear& lin, int k, const int32_t* k_dev,
   return DPLLM_OK;
 }
 
-// one linear, B right-hand sides: a batch runs in groups of two samples that share one pass over the planes
+// one linear, B right-hand sides: a batch runs in groups of four samples that share one pass over the planes
 int launch_gemv(dpllm_model* m, const Linear& lin, int k, const int32_t* k_dev, const void* x, void* y, int B, hipStream_t st) {
   const bool streaming = k_dev ? lin.L.kmin >= kFastKMin : (k >= kFastKMin && k <= kFastKMax);
   if (!streaming) return launch_plain(m, lin, k, k_dev, x, y, B, st);
   GemvJob j = make_gemv_job(lin, k, k_dev, x, y);
   const int rpb = pick_blocks_per_group(lin.L, k_dev ? lin.L.p : k, lin.L.nrq);
   j.nblocks = (lin.L.nrq + rpb - 1) / rpb;
-  const long groups = B > 1 ? (B + 1) / 2 : 1, per_pass = B > 1 ? 2 : 1;
+  const long groups = B > 1 ? (B + 3) / 4 : 1, per_pass = B > 1 ? 4 : 1;
   if (m->ws.base) {   // without a workspace there is no pool for partial sums: no column split
     j.nsplit = pick_lane_split(lin.L, j.nblocks * groups, (long)lin.L.nrq * per_pass * groups, kLanePoolRows);
     j.nblocks *= j.nsplit;
@@ -344,7 +344,7 @@ int launch_gemv(dpllm_model* m, const Linear& lin, int k, const int32_t* k_dev, 
     j.cnt = m->ws.at<uint32_t>(m->ws.lane_cnt);
   }
   if (B > 1)
-    hipLaunchKernelGGL((gemv_lane_kernel<2>), dim3(j.nblocks * (unsigned)groups), dim3(kLaneThreads), 0, st, (const GemvJob*)nullptr,
+    hipLaunchKernelGGL((gemv_lane_kernel<4>), dim3(j.nblocks * (unsigned)groups), dim3(kLaneThreads), 0, st, (const GemvJob*)nullptr,
                        (const int32_t*)nullptr, B, j, (const SelParams*)nullptr, (const int32_t*)nullptr, 0);
   else
     hipLaunchKernelGGL((gemv_lane_kernel<1>), dim3(j.nblocks), dim3(kLaneThreads), 0, st, (const GemvJob*)nullptr,

@@ -1,7 +1,7 @@
-// Any-precision GEMV for gfx950, row-per-lane variant: y[o] = sum_c LUT_k[o][code_k(o,c)] * x[c]   (paper Sec. 3:
+// Any-precision GEMV for gfx950, one row per lane: y[o] = sum_c LUT_k[o][code_k(o,c)] * x[c]   (paper Sec. 3:
 // the linear operation of a decode step; Sec. 2.2: the k-bit model is the top k planes of the parent).
 //
-// Layout (kLayoutRowLane): a plane is cut into tiles of 64 rows x 128 columns; lane l of a wavefront owns row
+// Layout: a plane is cut into tiles of 64 rows x 128 columns; lane l of a wavefront owns row
 // 64 rb + l of the tile and reads its four 32-column words with one 128-bit load, so a wavefront load is 1 KiB
 // of contiguous memory per plane.  Words are permuted and rotated as in layout_device.hpp.
 //
@@ -10,17 +10,24 @@
 // lookups are free of bank conflicts whatever the table size; the two-weight tables of k = 3 and k = 4, which
 // cost 4 - 6 LDS cycles per lookup when a whole wavefront shares one row's table, cost 2.
 // The activations are the same for all lanes.  With every tile a lane fetches one dword of them (256 bytes per
-// wavefront); before the tile is decoded the wavefront parks them in a private LDS slot and every lane reads
-// back 16 bytes per word (lane l takes the pairs 4 (l mod 4) .. + 3).  A wavefront with at most four tiles per
-// row block (rows up to 4096 columns) parks them once for its whole run instead.  The multiply-add reads the pair it
-// needs from the right lane of its quad with a DPP quad broadcast: 16 registers hold the 64 pairs of a tile.
+// wavefront); before the tile is decoded the wavefront parks them in a private LDS slot.  A wavefront with at
+// most four tiles per row block (rows up to 4096 columns) parks them once for its whole run instead.
+// The multiply-adds run on the matrix pipe, as lane-private dot products: v_mfma_f32_4x4x4_16b_f16 works on 16
+// blocks of four lanes; with the A operand of one block broadcast to all blocks (cbsz = 4, abid = Q) lane L gets
+//     acc[i] += sum_n A(lane 4 Q + i)[n] * B(lane L)[n],  n = 0 .. 3,  i = 0 .. 3.
+// B = four looked-up weights of the lane's own row; A = the four activations that go with them, held by the
+// lanes of quad Q.  Quad Q of the wavefront holds chunks Q and 16 + Q of the tile's 32 chunks of four
+// activations: 4 registers carry the 128 activations of a tile, and one matrix instruction (one issue slot of
+// the vector unit, the arithmetic overlaps with the vector instructions of other wavefronts) does the work of
+// two packed dot products.  The four lanes of a quad may hold four different samples: lane 4 Q + i holds sample
+// i's chunk and acc[i] is sample i's sum, so up to four right-hand sides share a pass at the cost of one (with
+// one sample the four lanes hold the same chunk and the four sums are equal).
 // Each lane accumulates its own row: no cross-lane reduction.  A workgroup is eight wavefronts that split the
 // columns of the same 64 rows and share the tables; their eight partial sums per row meet in LDS.
-// Two right-hand sides can share a pass: every lookup then feeds two multiply-adds.
 //
 //   k = 3, 4 : two weights per lookup, tables of 64 / 256 fp16 pairs per row (16 / 64 KiB per workgroup)
-//   k >= 5   : one weight per lookup (table of 2^k entries per row, 8 .. 64 KiB), two results packed for one
-//              v_dot2_f32_f16
+//   k >= 5   : one weight per lookup (table of 2^k entries per row, 8 .. 64 KiB), two results packed into one
+//              register of the B operand
 // One kernel serves every bitwidth from 3 to 8: a workgroup reads the bitwidth of its job (a value, or the word a
 // selector wrote in device memory) and branches to the code of that bitwidth.  Every branch stays below 128 vector
 // registers and the workgroup's LDS is sized for the largest tables (64 KiB), so two workgroups share a compute
@@ -29,6 +36,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "gemv_common.hpp"
 #include "layout_device.hpp"
@@ -51,31 +59,35 @@ struct LaneDecode {
   __host__ __device__ static constexpr int rot(int c) { return (c + 1) & 7; }
   __host__ __device__ static constexpr int byte(int col) { return ((top(col) - rot(word(col))) & 31) >> 3; }
 };
-constexpr int kLaneRedBytes = kLaneWaves * 64 * 4;            // the partial sums of the eight wavefronts
+constexpr int kLaneRedBytes = kLaneWaves * 64 * 4;            // the partial sums of the eight wavefronts, per sample
 constexpr int kLaneKeepTiles = 4;                             // a wavefront with so few tiles per row block keeps their activations in LDS
-constexpr int kLaneXBytes = 512 + kLaneKeepTiles * 256;       // per wavefront: a tile's activations (natural, ready), kept tiles
 constexpr int kLaneTableBytes = 65536;                        // the largest tables: k = 4 (pairs) and k = 8
 static_assert(LaneDecode<3>::table_bytes <= kLaneTableBytes && LaneDecode<4>::table_bytes <= kLaneTableBytes &&
               LaneDecode<5>::table_bytes <= kLaneTableBytes && LaneDecode<6>::table_bytes <= kLaneTableBytes &&
               LaneDecode<7>::table_bytes <= kLaneTableBytes && LaneDecode<8>::table_bytes <= kLaneTableBytes, "tables fit");
-// NB right-hand sides per pass (1 or 2): NB sets of partial sums; with two, every sample has a 512-byte slot per
-// wavefront and nothing is kept across row blocks
+// NB right-hand sides per pass (1 or 4).  Per wavefront: a 256-byte slot for the parked activations of a tile per
+// sample; with one sample, four more for the tiles it keeps across row blocks.
 template <int NB>
-__host__ __device__ constexpr int lane_x_bytes() { return NB == 1 ? kLaneXBytes : NB * 512; }
-// tables, partial sums, activation slots, and one word for the column-split hand-over
+__host__ __device__ constexpr int lane_x_bytes() { return NB == 1 ? 256 + kLaneKeepTiles * 256 : NB * 256; }
+// tables, partial sums, activation slots.  Two things borrow space from the partial sums while these are not in
+// use (between the barrier that opens a row block and the stores that close it): the 256 bytes a wavefront needs
+// to re-pair the activations at k = 4 (its own partial sums of sample 0), and the word of the column-split
+// hand-over (the first word; written after every reader of the partial sums has passed a barrier).  With four
+// samples the total is exactly half of a compute unit's LDS.
 template <int NB>
-__host__ __device__ constexpr int lane_flag_offset() { return kLaneTableBytes + NB * kLaneRedBytes + kLaneWaves * lane_x_bytes<NB>(); }
-template <int NB>
-__host__ __device__ constexpr int lane_lds_bytes() { return lane_flag_offset<NB>() + 16; }
+__host__ __device__ constexpr int lane_lds_bytes() { return kLaneTableBytes + NB * kLaneRedBytes + kLaneWaves * lane_x_bytes<NB>(); }
+static_assert(lane_lds_bytes<4>() <= 81920 && lane_lds_bytes<1>() <= 81920, "two workgroups per compute unit");
 
-// x pair held by lane Q of the quad, times the looked-up pair, added to acc
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// acc[i] += sum_n x(lane 4 Q + i)[n] * w[n]: x = four fp16 (what this lane holds matters to the lanes whose Q is
+// this lane's quad), w = the four weights {w0.lo, w0.hi, w1.lo, w1.hi} of this lane's row
 template <int Q>
-__device__ __forceinline__ void dot2_quad(float& acc, uint32_t xreg, uint32_t wpair) {
-  static_assert(Q >= 0 && Q < 4, "quad lane");
-  if constexpr (Q == 0) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
-  if constexpr (Q == 1) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
-  if constexpr (Q == 2) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
-  if constexpr (Q == 3) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+__device__ __forceinline__ void mfma_chunk(f32x4& acc, uint64_t x, uint32_t w0, uint32_t w1) {
+  static_assert(Q >= 0 && Q < 16, "quad of the wavefront");
+  const uint64_t w = (uint64_t)w0 | ((uint64_t)w1 << 32);
+  acc = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4, x), __builtin_bit_cast(f16x4, w), acc, 4, Q, 0);
 }
 
 // LDS address of entry (byte N of t) in the lane's table column: byte 1 = the entry, byte 0 = lane * 4
@@ -135,8 +147,9 @@ __device__ __forceinline__ void lane_load_tile(LaneTile<K, NB>& t, const GemvJob
   }
 }
 
-// Parks a tile's activations in LDS in the form the lanes read back: 64 dwords, dword 16 j + 4 q + m = pair
-// 4 q + m of word j.  k != 4: the natural pairs (2i, 2i+1), so the lane's dword goes straight to `ready`.
+// Parks a tile's activations in LDS in the form the lanes read back: 64 dwords, dword 16 j + n = pair n of word
+// j; chunk g of the tile (dwords 2 g, 2 g + 1) goes with the lookups of pairs 2 (g mod 8), + 1 of word g / 8.
+// k != 4: the natural pairs (2i, 2i+1), so the lane's dword goes straight to `ready`.
 // k = 4: the pairs (x[col_hi], x[col_lo]) of merged word q, byte m (see nibble_pair_col_hi / _lo), cut from a
 // natural copy in `scratch`.
 template <int K>
@@ -198,17 +211,15 @@ __device__ __forceinline__ void lane_issue_pairs(const uint32_t (&T)[4], uint32_
   }
 }
 
-// last lookup first: LDS answers in issue order, so one counter wait covers the eight
-template <int JA>
-__device__ __forceinline__ void lane_consume_pairs(const uint32_t (&v)[8], const u32x4& x, float (&acc)[4]) {
-  dot2_quad<JA + 1>(acc[3], x.w, v[7]);
-  dot2_quad<JA + 1>(acc[2], x.z, v[6]);
-  dot2_quad<JA + 1>(acc[1], x.y, v[5]);
-  dot2_quad<JA + 1>(acc[0], x.x, v[4]);
-  dot2_quad<JA>(acc[3], x.w, v[3]);
-  dot2_quad<JA>(acc[2], x.z, v[2]);
-  dot2_quad<JA>(acc[1], x.y, v[1]);
-  dot2_quad<JA>(acc[0], x.x, v[0]);
+// The eight lookups of entry words JA, JA + 1 of word j (JO = j mod 2) are the chunks 8 JO + 2 JA .. + 3 of the
+// tile's half j / 2, whose activations x holds.  Last lookup first: LDS answers in issue order, so one counter
+// wait covers the eight.  Two sets of sums take turns, so that no matrix instruction waits for the one before it.
+template <int JA, int JO>
+__device__ __forceinline__ void lane_consume_pairs(const uint32_t (&v)[8], uint64_t x, f32x4 (&acc)[2]) {
+  mfma_chunk<8 * JO + 2 * JA + 3>(acc[1], x, v[6], v[7]);
+  mfma_chunk<8 * JO + 2 * JA + 2>(acc[0], x, v[4], v[5]);
+  mfma_chunk<8 * JO + 2 * JA + 1>(acc[1], x, v[2], v[3]);
+  mfma_chunk<8 * JO + 2 * JA + 0>(acc[0], x, v[0], v[1]);
 }
 
 // single-weight schemes: the eight lookups of columns 8 JJ .. 8 JJ + 7
@@ -225,13 +236,12 @@ __device__ __forceinline__ void lane_issue_singles(const uint32_t (&R)[8], uint3
 #undef DPLLM_LANE_LOOKUP
 }
 
-// a table entry is an fp16 in the low half of a dword: two of them pack into one fp16 pair
-template <int JJ>
-__device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], const u32x4& x, float (&acc)[4]) {
-  dot2_quad<JJ>(acc[3], x.w, v[6] | (v[7] << 16));
-  dot2_quad<JJ>(acc[2], x.z, v[4] | (v[5] << 16));
-  dot2_quad<JJ>(acc[1], x.y, v[2] | (v[3] << 16));
-  dot2_quad<JJ>(acc[0], x.x, v[0] | (v[1] << 16));
+// a table entry is an fp16 in the low half of a dword: two of them pack into one fp16 pair; columns 8 JJ .. + 7 of
+// word j (JO = j mod 2) are the chunks 8 JO + 2 JJ, + 1
+template <int JJ, int JO>
+__device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], uint64_t x, f32x4 (&acc)[2]) {
+  mfma_chunk<8 * JO + 2 * JJ + 1>(acc[1], x, v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+  mfma_chunk<8 * JO + 2 * JJ + 0>(acc[0], x, v[0] | (v[1] << 16), v[2] | (v[3] << 16));
 }
 
 // k = 5, 6: the merge tree with its masks in vector registers (full-rate instructions); k = 7, 8 have no registers
@@ -244,16 +254,17 @@ __device__ __forceinline__ void lane_merge_fields(const uint32_t (&w)[K], uint32
 
 // ---- one tile -------------------------------------------------------------------------------------------------
 // Lookups run in chunks of eight; the next chunk's lookups are issued before the current chunk's multiply-adds.
-// xready: the parked activations of sample 0; sample b at + b * xstep
+// xmine: where this lane finds its chunk of the parked activations of the tile's first half (its sample's slot +
+// 8 * (lane / 4)); the chunk of the second half is 128 bytes on
 template <int K, int NB>
-__device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t lanecol, int lane, const char* lds, const char* xready,
-                                             int xstep, float (&acc)[NB][4], uint32_t (&addr)[8], uint32_t mask, const MergeMasks<K>& M) {
+__device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t lanecol, const char* lds, const char* xmine,
+                                             f32x4 (&acc)[2], uint32_t (&addr)[8], uint32_t mask, const MergeMasks<K>& M) {
   uint32_t va[8], vb[8];
-  u32x4 xq[NB][4];   // xq[b][j][m] = pair 4 q + m of word j of sample b, q = lane mod 4
-#pragma unroll
-  for (int b = 0; b < NB; ++b)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) xq[b][j] = *reinterpret_cast<const u32x4*>(xready + b * xstep + j * 64 + (lane & 3) * 16);
+  const uint64_t xa[2] = {*reinterpret_cast<const uint64_t*>(xmine), *reinterpret_cast<const uint64_t*>(xmine + 128)};
+  using J0 = std::integral_constant<int, 0>;
+  using J1 = std::integral_constant<int, 1>;
+  using J2 = std::integral_constant<int, 2>;
+  using J3 = std::integral_constant<int, 3>;
   if constexpr (LaneDecode<K>::pair) {
     uint32_t T[4][4];
 #pragma unroll
@@ -266,23 +277,18 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t 
       }
     }
     lane_issue_pairs<0, K == 3>(T[0], lanecol, lds, va, addr, mask);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    auto word = [&](auto jc) {
+      constexpr int j = decltype(jc)::value;
       lane_issue_pairs<2, K == 3>(T[j], lanecol, lds, vb, addr, mask);
       sched_fence();
-      {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) lane_consume_pairs<0>(va, xq[b][j], acc[b]);
-      }
+      lane_consume_pairs<0, j & 1>(va, xa[j >> 1], acc);
       sched_fence();
-      if (j + 1 < 4) lane_issue_pairs<0, K == 3>(T[j + 1], lanecol, lds, va, addr, mask);
+      if constexpr (j + 1 < 4) lane_issue_pairs<0, K == 3>(T[j + 1], lanecol, lds, va, addr, mask);
       sched_fence();
-      {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) lane_consume_pairs<2>(vb, xq[b][j], acc[b]);
-      }
+      lane_consume_pairs<2, j & 1>(vb, xa[j >> 1], acc);
       sched_fence();
-    }
+    };
+    word(J0{}); word(J1{}); word(J2{}); word(J3{});
   } else {
     uint32_t R[2][8];
     {
@@ -292,43 +298,32 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t 
       lane_merge_fields<K>(w, R[0], M);
     }
     lane_issue_singles<K, 0>(R[0], lanecol, lds, va);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (j + 1 < 4) {
+    auto word = [&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      if constexpr (j + 1 < 4) {
         uint32_t w[K];
 #pragma unroll
-        for (int b = 0; b < K; ++b) w[b] = t.w[b][(j + 1) & 3];
+        for (int b = 0; b < K; ++b) w[b] = t.w[b][j + 1];
         lane_merge_fields<K>(w, R[(j + 1) & 1], M);
       }
       lane_issue_singles<K, 1>(R[j & 1], lanecol, lds, vb);
       sched_fence();
-      {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) lane_consume_singles<0>(va, xq[b][j], acc[b]);
-      }
+      lane_consume_singles<0, j & 1>(va, xa[j >> 1], acc);
       sched_fence();
       lane_issue_singles<K, 2>(R[j & 1], lanecol, lds, va);
       sched_fence();
-      {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) lane_consume_singles<1>(vb, xq[b][j], acc[b]);
-      }
+      lane_consume_singles<1, j & 1>(vb, xa[j >> 1], acc);
       sched_fence();
       lane_issue_singles<K, 3>(R[j & 1], lanecol, lds, vb);
       sched_fence();
-      {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) lane_consume_singles<2>(va, xq[b][j], acc[b]);
-      }
+      lane_consume_singles<2, j & 1>(va, xa[j >> 1], acc);
       sched_fence();
-      if (j + 1 < 4) lane_issue_singles<K, 0>(R[(j + 1) & 1], lanecol, lds, va);
+      if constexpr (j + 1 < 4) lane_issue_singles<K, 0>(R[(j + 1) & 1], lanecol, lds, va);
       sched_fence();
-      {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) lane_consume_singles<3>(vb, xq[b][j], acc[b]);
-      }
+      lane_consume_singles<3, j & 1>(vb, xa[j >> 1], acc);
       sched_fence();
-    }
+    };
+    word(J0{}); word(J1{}); word(J2{}); word(J3{});
   }
 }
 
@@ -422,7 +417,8 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const uint32_t lanecol = (uint32_t)lane * 4;  // the lane's column of the interleaved tables
   float* red = reinterpret_cast<float*>(lds + table_bytes);
-  char* slot = lds + table_bytes + NB * kLaneRedBytes + wave * lane_x_bytes<NB>();
+  char* ready = lds + table_bytes + NB * kLaneRedBytes + wave * lane_x_bytes<NB>();   // + 256 b: the parked tile of sample b
+  char* repair = reinterpret_cast<char*>(red) + wave * 256;   // k = 4: room to re-pair a tile's activations (see lane_lds_bytes)
   const int nsplit = job.nsplit;
   const int slice = split * kLaneWaves + wave, nslices = nsplit * kLaneWaves;
   const int c0 = slice * job.ncc / nslices, c1 = (slice + 1) * job.ncc / nslices;
@@ -441,7 +437,9 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   // tiles are asked for after the activations have been parked)
   constexpr bool kEarlyX = K != 4;
   const bool keep = NB == 1 && c1 - c0 <= kLaneKeepTiles;
-  char* kept = slot + 512;
+  char* kept = ready + 256;
+  // this lane's view of the parked activations: its sample's slot (lane mod 4, with several samples), its quad's chunk
+  const int xlane = (NB == 1 ? 0 : (lane & 3) * 256) + (lane >> 2) * 8;
   uint32_t xkeep[kLaneKeepTiles];
   if (keep) {
     if constexpr (kEarlyX) {
@@ -449,7 +447,7 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       for (int i = 0; i < kLaneKeepTiles; ++i) xkeep[i] = lane_load_x(job, min(c0 + i, job.ncc - 1), lane);
     } else {
       for (int cc = c0; cc < c1; ++cc)
-        lane_park_x<K>(lane_mask_x(job, cc, lane, lane_load_x(job, cc, lane)), lane, slot, kept + (cc - c0) * 256);
+        lane_park_x<K>(lane_mask_x(job, cc, lane, lane_load_x(job, cc, lane)), lane, repair, kept + (cc - c0) * 256);
     }
   }
   if constexpr (kLutAhead) lane_fetch_lut<K>(L, lut_base, block, lane, wave);
@@ -469,11 +467,10 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   if (kEarlyX && keep) {
 #pragma unroll
     for (int i = 0; i < kLaneKeepTiles; ++i)
-      if (c0 + i < c1) lane_park_x<K>(lane_mask_x(job, c0 + i, lane, xkeep[i]), lane, slot, kept + i * 256);
+      if (c0 + i < c1) lane_park_x<K>(lane_mask_x(job, c0 + i, lane, xkeep[i]), lane, repair, kept + i * 256);
   }
-  float acc[NB][4];
-#pragma unroll
-  for (int b = 0; b < NB; ++b) acc[b][0] = acc[b][1] = acc[b][2] = acc[b][3] = 0.f;
+  f32x4 acc[2];   // two sets that take turns; [i] = the sum of sample i (one sample: four equal sums)
+  acc[0] = acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
   MergeMasks<K> M;
   if constexpr (K <= 6) M.init();
   uint32_t addr[8], mask = 0x3fu;              // k = 3: address registers of the lookups (see lane_issue_pairs)
@@ -488,10 +485,8 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   };
   auto close_block = [&]() {
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      red[(b * kLaneWaves + wave) * 64 + lane] = (acc[b][0] + acc[b][1]) + (acc[b][2] + acc[b][3]);
-      acc[b][0] = acc[b][1] = acc[b][2] = acc[b][3] = 0.f;
-    }
+    for (int b = 0; b < NB; ++b) red[(b * kLaneWaves + wave) * 64 + lane] = acc[0][b] + acc[1][b];
+    acc[0] = acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
     lane_group_barrier();
     const bool storer = wave < NB && (NB == 1 || wave < job.nsamples);   // wavefront b stores sample b
     float s = 0.f;
@@ -510,7 +505,7 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       // fence drops what this die may still cache of the pool before the sums are read.
       DPLLM_GLOBAL float* part = as_global(job.ws) + (size_t)(rb * NB + wave) * nsplit * 64 + lane;
       DPLLM_GLOBAL uint32_t* ticket = as_global(job.cnt) + rb * NB;
-      uint32_t* flag = reinterpret_cast<uint32_t*>(lds + lane_flag_offset<NB>());
+      uint32_t* flag = reinterpret_cast<uint32_t*>(red);   // free by now: the sums above were read before the next barrier
       if (storer) part[split * 64] = s;
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __builtin_amdgcn_s_barrier();
@@ -553,10 +548,10 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
       const char* xready = kept + (cc - c0) * 256;
       if (!keep) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) lane_park_x<K>(lane_mask_x(job, cc, lane, ring[s].x[b]), lane, slot + b * 512, slot + b * 512 + 256);
-        xready = slot + 256;
+        for (int b = 0; b < NB; ++b) lane_park_x<K>(lane_mask_x(job, cc, lane, ring[s].x[b]), lane, repair, ready + b * 256);
+        xready = ready;
       }
-      lane_compute<K, NB>(ring[s], lanecol, lane, lds, xready, 512, acc, addr, mask, M);
+      lane_compute<K, NB>(ring[s], lanecol, lds, xready + xlane, acc, addr, mask, M);
       if (++cc >= c1) {
         close_block();
         rb += step;
