@@ -277,6 +277,9 @@ GemvJob make_gemv_job(const Linear& lin, int k, const int32_t* k_dev, const void
 // end of the launch (measured on the 7B step: 0.25 MiB 496 us, 0.375 MiB 480, 0.75 MiB 471, 1 MiB 468, 2 MiB
 // 477, 4 MiB 546); and a launch wants at least a few workgroups per compute unit.
 constexpr long kLaneGroupBytes = 1048576;
+// GEMV launches below this many workgroups take their selectors' decisions themselves; larger ones get a launch
+// of its own for the decisions (measured on a 7B step of 3094 workgroups: 509 against 514 us)
+constexpr int kFoldMaxBlocks = 1536;
 constexpr int kLaneSplitBlocks = 256;   // a launch that splits columns aims at one workgroup per compute unit
 int pick_blocks_per_group(const LinearLayout& L, int k, long total_blocks, long group_bytes = kLaneGroupBytes) {
   const long bytes_per_block = 64L * L.in * k / 8;
@@ -920,28 +923,31 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
   }
   const Workspace& W = m->ws;
   SelJob none{};
-  SelParams pnone{};
   GemvJob gnone{};
+  SelParams pnone{};
   const SelParams* d_params = W.at<SelParams>(W.sel_params);
   const int32_t* d_target = W.at<int32_t>(W.target);
   const bool both = parts == (DPLLM_STEP_SELECT | DPLLM_STEP_GEMV);
   for (const Phase& ph : P.phases) {
+    const bool fold = both && !ph.decide && ph.blocks < kFoldMaxBlocks;
     if ((parts & DPLLM_STEP_SELECT) && ph.sel_count > 0) {
       const SelJob* jobs = W.at<SelJob>(W.sel_jobs) + ph.sel_first;
       if (ph.estimators)
         hipLaunchKernelGGL(selector_part_kernel, dim3(ph.part_count), dim3(kSelPartThreads), 0, st, jobs,
                            (const SelPart*)(W.at<SelPart>(W.sel_parts) + ph.part_first),
                            (const int32_t*)(W.at<int32_t>(W.sel_members) + ph.member_first), d_params, d_target, n, none, pnone);
-      // Whole step: the GEMV workgroups take the decisions of their linears themselves.  Selectors alone, or a
-      // linear on the plain kernel: a launch that finishes every job of this selector launch.
-      if (!both || ph.decide)
+      // Whole step: the GEMV workgroups take the decisions of their linears themselves (one launch fewer per
+      // dependency level).  Selectors alone, a linear on the plain kernel, or a GEMV launch of so many workgroups
+      // that repeating the decision in each of them costs more than a launch: a launch that finishes every job of
+      // this selector launch.
+      if (!fold)
         hipLaunchKernelGGL(selector_decide_kernel, dim3(ph.sel_count), dim3(kSelDecideThreads), 0, st, jobs, d_params, d_target, n, none, pnone);
     }
     if (!(parts & DPLLM_STEP_GEMV)) continue;
     if (ph.gemv_count > 0)
       hipLaunchKernelGGL((gemv_lane_kernel<1>), dim3(ph.blocks), dim3(kLaneThreads), 0, st,
                          (const GemvJob*)(W.at<GemvJob>(W.gemv_jobs) + ph.gemv_first), (const int32_t*)(W.at<int32_t>(W.block_jobs) + ph.block_first),
-                         ph.gemv_count, gnone, both ? d_params : (const SelParams*)nullptr, d_target, n);
+                         ph.gemv_count, gnone, fold ? d_params : (const SelParams*)nullptr, d_target, n);
     for (int j : ph.plain) {
       int rc = launch_plain(m, m->linears[j], 0, k_dev + j, xs[j], ys[j], 1, st);
       if (rc != DPLLM_OK) return rc;
