@@ -63,6 +63,8 @@ def main():
                          "used with --sections step for per-bitwidth counter profiles")
     ap.add_argument("--sections", default=",".join(ALL_SECTIONS), help="comma list of " + ", ".join(ALL_SECTIONS))
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only (no HIP graph replay)")
+    ap.add_argument("--sustain", type=float, default=3.0,
+                    help="seconds of back-to-back graph replays behind the 'sustained' figure (0: skip)")
     ap.add_argument("--copy-yardstick", action="store_true",
                     help="also run a plain 1 GiB copy kernel (for scaling hardware byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -138,8 +140,10 @@ def main():
             calls += steps
         return total / calls
 
-    def timed_graph(fn, steps, min_ms=MIN_TIMED_MS):
-        """ms per call with `steps` calls of fn recorded once in a HIP graph and the graph replayed."""
+    def timed_graph(fn, steps, min_ms=MIN_TIMED_MS, sustain_s=0.0):
+        """ms per call with `steps` calls of fn recorded once in a HIP graph and the graph replayed.  sustain_s > 0:
+        also replays for that many seconds and returns the ms per call over the last third of them (the chip's
+        clocks depend on how long it has been under load), else None."""
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for t in range(steps):
@@ -155,7 +159,19 @@ def main():
             torch.cuda.synchronize()
             total += e0.elapsed_time(e1)
             reps += 1
-        return total / (reps * steps), reps
+        sustained = None
+        if sustain_s > 0:
+            per_replay = total / reps
+            n_all = max(3, int(sustain_s * 1e3 / per_replay))
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for r in range(n_all):
+                if r == n_all - n_all // 3:
+                    e0.record()
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            sustained = e0.elapsed_time(e1) / ((n_all // 3) * steps)
+        return total / (reps * steps), reps, sustained
 
     if args.pin_k is not None:
         for i in range(n):
@@ -172,11 +188,11 @@ def main():
     full_step(0)
     torch.cuda.synchronize()
     ms_step_eager = timed(full_step, args.steps, args.warmup)
-    ms_step, launch_mode, timed_steps = ms_step_eager, "eager launches", args.steps
+    ms_step, launch_mode, timed_steps, ms_sustained = ms_step_eager, "eager launches", args.steps, None
     if not args.no_graph:
         # the same K steps recorded once in a HIP graph (per step: one input copy + two kernels) and replayed:
         # what a serving loop does to shed launch gaps.  The replay's final state is checked against eager.
-        ms_graph, reps = timed_graph(lambda t: full_step(args.warmup + t), args.steps)
+        ms_graph, reps, _ = timed_graph(lambda t: full_step(args.warmup + t), args.steps)
         k_graph, y_graph = k_dev.clone(), y_tensors[-1].clone()
         full_step(args.warmup + args.steps - 1)
         torch.cuda.synchronize()
@@ -337,7 +353,7 @@ def main():
                 for B in batches:
                     xb = X[0].contiguous() if B == 1 else X[:B].contiguous()
                     yb = ybatch[0] if B == 1 else ybatch[:B]
-                    ms, _ = timed_graph(lambda t: m2.dpllm_gemv(t % copies, k, xb, y=yb), copies)
+                    ms = timed_graph(lambda t: m2.dpllm_gemv(t % copies, k, xb, y=yb), copies)[0]
                     key = "us_isolated" if B == 1 else "us_B%d" % B
                     entry[key] = round(ms * 1e3, 3)
                     entry["GBps_isolated" if B == 1 else "GBps_B%d" % B] = round(gemv_bytes(o, i, k, B) / (ms * 1e-3) / 1e9, 1)
@@ -390,6 +406,12 @@ def main():
                "sample": ("%d whole decode steps (all %d linears), %.1f s of CPU time" % (reps, n, dt)) if whole else
                          ("block 0 of %d (7 linears), %d steps, %.1f s; us_per_decode_step is that x %d" % (args.blocks, reps, dt, args.blocks))}
 
+    # ---- last, so that nothing else is measured on a chip it has warmed up: the step's graph replayed for seconds --
+    if args.sustain > 0 and not args.no_graph and "step" in sections:
+        full_step(0)                                   # back to the plan of the unchained step
+        torch.cuda.synchronize()
+        ms_sustained = timed_graph(lambda t: full_step(args.warmup + t), args.steps, min_ms=0.0, sustain_s=args.sustain)[2]
+        log("sustained: %.1f us/step over the last third of %.1f s" % (ms_sustained * 1e3, args.sustain))
     out = {
         "metric": "any-precision GEMV HBM GB/s (whole decode step at ~%.2f average bits, selectors included)" % eff_bits,
         "value": round(bytes_step / (ms_step * 1e-3) / 1e9, 1),
@@ -416,6 +438,9 @@ def main():
         "us_per_decode_step": round(ms_step * 1e3, 1),
         "us_per_decode_step_eager": round(ms_step_eager * 1e3, 1),
         "launch": launch_mode,
+        "sustained": None if ms_sustained is None else {
+            "us_per_decode_step": round(ms_sustained * 1e3, 1), "seconds": args.sustain,
+            "note": "the same graph replayed back to back for this long, timed over the last third"},
         "effective_bits": round(eff_bits, 4),
         "bytes_per_step": int(bytes_step),
         "selector": {"us_per_step": round(ms_sel * 1e3, 1), "GBps": round(sel_bytes / (ms_sel * 1e-3) / 1e9, 1),

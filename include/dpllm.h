@@ -188,6 +188,9 @@ int dpllm_gemv(dpllm_model* m, int id, int k, const int32_t* k_dev, const void* 
  * thresholds, pairs in use or target entries changed copies the parameter table.  Both are
  * asynchronous copies on `stream` (nothing is synchronised, nothing allocated) but cannot
  * be captured into a graph: ESTATE then.  Every other call only enqueues kernels.
+ * A graph that holds captured steps reads these tables when it is replayed: it follows later changes of
+ * thresholds, pairs in use, target entries and the target (that is the point of keeping them on the device),
+ * and it must not be replayed after a call that rebuilt the launch plan for other pointers or shapes.
  * Errors: EINVAL, ESTATE, ESHAPE, EHIP. */
 int dpllm_decode_step(dpllm_model* m, const void* const* xs, void* const* ys, int32_t* k_dev,
                       float* e_dev, void* stream);
