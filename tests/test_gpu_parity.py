@@ -127,7 +127,7 @@ def test_gemv_llama7b_shapes_k3_to_8(dp, out, in_):
 
 @pytest.mark.parametrize("B", [2, 3, 4, 5, 7, 8])
 def test_gemv_small_batch(dp, B):
-    """Groups of two or four samples share one pass over the planes; ragged last group, ragged last strip."""
+    """Groups of up to four samples share one pass over the planes; ragged last group, ragged last tile."""
     in_ = 4096 + 96
     lin = synth.make_linear(260, in_, 8, 3, seed=B)
     model = load(dp, [lin])
