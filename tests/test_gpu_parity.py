@@ -571,8 +571,54 @@ def test_abi_error_paths(dp):
     import ctypes as C
     n = C.c_size_t(0)
     assert dp.lib.dpllm_linear_device_bytes(8, 48, 4, 3, C.byref(n)) == dp.DPLLM_ESHAPE
+    # x and y of one GEMV must not overlap
+    buf = torch.zeros(128, dtype=torch.float16, device="cuda")
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_gemv(0, 3, buf[:64], y=buf[56:64])
+    assert ei.value.code == dp.DPLLM_EINVAL
+    # targets: 1 .. DPLLM_MAX_TARGETS - 1 hold entries, the pair of an entry must have been attached
+    model.dpllm_set_selector(0, 3, 4, dp.DPLLM_SEL_LINREG, alpha=1.0, beta=0.0, T=1.0)
+    for bad in (0, dp.DPLLM_MAX_TARGETS, -1):
+        with pytest.raises(dp.DpllmError) as ei:
+            model.dpllm_set_target_entry(bad, 0, 3, 4, 1.0)
+        assert ei.value.code == dp.DPLLM_EINVAL
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_set_target_entry(1, 0, 3, 3, 1.0)          # pair (3,3) was never attached
+    assert ei.value.code == dp.DPLLM_ESTATE
+    with pytest.raises(dp.DpllmError) as ei:
+        model.dpllm_set_target_entry(1, 0, 3, 4, float("nan"))
+    assert ei.value.code == dp.DPLLM_EINVAL
+    for bad in (-1, dp.DPLLM_MAX_TARGETS):
+        with pytest.raises(dp.DpllmError) as ei:
+            model.dpllm_set_target(bad)
+        assert ei.value.code == dp.DPLLM_EINVAL
+    # the workspace: too small, misaligned; a step, an estimate and a target switch without one
+    need = model.dpllm_workspace_bytes()
+    small = torch.empty(need, dtype=torch.uint8, device="cuda")
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert dp.lib.dpllm_set_workspace(model.h, C.c_void_p(small.data_ptr()), C.c_size_t(need - 256), stream) == dp.DPLLM_ESTATE
+    assert dp.lib.dpllm_set_workspace(model.h, C.c_void_p(small.data_ptr() + 16), C.c_size_t(need), stream) == dp.DPLLM_EINVAL
+    bare = dp.Model(1)
+    bare.dpllm_load_linear(0, synth.planes_np(lin["planes"]), {k: synth.lut_np(v) for k, v in lin["luts"].items()}, 3)
+    bare.dpllm_set_selector(0, 3, 4, dp.DPLLM_SEL_LINREG, alpha=1.0, beta=0.0, T=1.0)
+    assert bare.workspace is None
+    assert dp.lib.dpllm_set_target(bare.h, 1, stream) == dp.DPLLM_ESTATE
+    e1 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    k1 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert dp.lib.dpllm_estimate(bare.h, 0, 3, 4, C.c_void_p(x.data_ptr()), C.c_void_p(e1.data_ptr()), C.c_void_p(k1.data_ptr()),
+                                 stream) == dp.DPLLM_ESTATE
+    y8 = torch.zeros(8, dtype=torch.float16, device="cuda")
+    xs1, ys1 = (C.c_void_p * 1)(x.data_ptr()), (C.c_void_p * 1)(y8.data_ptr())
+    assert dp.lib.dpllm_decode_step(bare.h, xs1, ys1, C.c_void_p(k1.data_ptr()), C.c_void_p(e1.data_ptr()), stream) == dp.DPLLM_ESTATE
+    # ... while a GEMV needs none, and the entry point that allocates nothing neither
+    assert dp.lib.dpllm_gemv(bare.h, 0, 3, None, C.c_void_p(x.data_ptr()), C.c_void_p(y8.data_ptr()), 1, stream) == dp.DPLLM_OK
+    assert dp.lib.dpllm_estimate_noalloc(bare.h, 0, 3, 4, C.c_void_p(x.data_ptr()), C.c_void_p(e1.data_ptr()),
+                                         C.c_void_p(k1.data_ptr()), stream) == dp.DPLLM_OK
+    torch.cuda.synchronize()
+    assert bare.workspace is None and int(k1.item()) == 3      # x = 0: estimate 0 <= T
     model.close()
     empty.close()
+    bare.close()
 
 
 # ----------------------------------------------------------------------------- T8 random shapes, long runs
