@@ -12,16 +12,17 @@
 // The activations are the same for all lanes.  With every tile a lane fetches one dword of them (256 bytes per
 // wavefront); before the tile is decoded the wavefront parks them in a private LDS slot.  A wavefront with at
 // most four tiles per row block (rows up to 4096 columns) parks them once for its whole run instead.
-// The multiply-adds run on the matrix pipe, as lane-private dot products: v_mfma_f32_4x4x4_16b_f16 works on 16
-// blocks of four lanes; with the A operand of one block broadcast to all blocks (cbsz = 4, abid = Q) lane L gets
+// One right-hand side (the decode step): every lane reads back 16 bytes per word (lane l takes the pairs
+// 4 (l mod 4) .. + 3) and the multiply-add v_dot2c_f32_f16 reads the pair it needs from the right lane of its quad
+// with a DPP quad broadcast: 16 registers hold the 64 pairs of a tile, fp32 accumulation in the lane.
+// Several right-hand sides (a small dense contraction: 64 rows x up to 4 samples per wavefront) run on the matrix
+// pipe instead: v_mfma_f32_4x4x4_16b_f16 works on 16 blocks of four lanes; with the A operand of one block
+// broadcast to all blocks (cbsz = 4, abid = Q) lane L gets
 //     acc[i] += sum_n A(lane 4 Q + i)[n] * B(lane L)[n],  n = 0 .. 3,  i = 0 .. 3.
 // B = four looked-up weights of the lane's own row; A = the four activations that go with them, held by the
-// lanes of quad Q.  Quad Q of the wavefront holds chunks Q and 16 + Q of the tile's 32 chunks of four
-// activations: 4 registers carry the 128 activations of a tile, and one matrix instruction (one issue slot of
-// the vector unit, the arithmetic overlaps with the vector instructions of other wavefronts) does the work of
-// two packed dot products.  The four lanes of a quad may hold four different samples: lane 4 Q + i holds sample
-// i's chunk and acc[i] is sample i's sum, so up to four right-hand sides share a pass at the cost of one (with
-// one sample the four lanes hold the same chunk and the four sums are equal).
+// lanes of quad Q: lane 4 Q + i holds sample i's chunk, acc[i] is sample i's sum.  Quad Q of the wavefront holds
+// chunks Q and 16 + Q of the tile's 32 chunks of four activations, so 4 registers carry a tile's activations and
+// every lookup serves four samples: up to four right-hand sides share a pass at the cost of one.
 // Each lane accumulates its own row: no cross-lane reduction.  A workgroup is eight wavefronts that split the
 // columns of the same 64 rows and share the tables; their eight partial sums per row meet in LDS.
 //
@@ -78,6 +79,16 @@ template <int NB>
 __host__ __device__ constexpr int lane_lds_bytes() { return kLaneTableBytes + NB * kLaneRedBytes + kLaneWaves * lane_x_bytes<NB>(); }
 static_assert(lane_lds_bytes<4>() <= 81920 && lane_lds_bytes<1>() <= 81920, "two workgroups per compute unit");
 
+// x pair held by lane Q of the quad, times the looked-up pair, added to acc
+template <int Q>
+__device__ __forceinline__ void dot2_quad(float& acc, uint32_t xreg, uint32_t wpair) {
+  static_assert(Q >= 0 && Q < 4, "quad lane");
+  if constexpr (Q == 0) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+  if constexpr (Q == 1) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+  if constexpr (Q == 2) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+  if constexpr (Q == 3) asm("v_dot2c_f32_f16_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xreg), "v"(wpair));
+}
+
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -89,6 +100,23 @@ __device__ __forceinline__ void mfma_chunk(f32x4& acc, uint64_t x, uint32_t w0, 
   const uint64_t w = (uint64_t)w0 | ((uint64_t)w1 << 32);
   acc = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4, x), __builtin_bit_cast(f16x4, w), acc, 4, Q, 0);
 }
+
+// The lane's partial sums.  One sample: four fp32 sums that take turns.  Four samples: two sets of four (sum i
+// of a set = sample i) that take turns, so that no matrix instruction waits for the one before it.
+template <int NB>
+struct LaneAcc;
+template <>
+struct LaneAcc<1> {
+  float v[4];
+  __device__ __forceinline__ void zero() { v[0] = v[1] = v[2] = v[3] = 0.f; }
+  __device__ __forceinline__ float sum(int) const { return (v[0] + v[1]) + (v[2] + v[3]); }
+};
+template <>
+struct LaneAcc<4> {
+  f32x4 v[2];
+  __device__ __forceinline__ void zero() { v[0] = v[1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+  __device__ __forceinline__ float sum(int b) const { return v[0][b] + v[1][b]; }
+};
 
 // LDS address of entry (byte N of t) in the lane's table column: byte 1 = the entry, byte 0 = lane * 4
 template <int N>
@@ -211,9 +239,23 @@ __device__ __forceinline__ void lane_issue_pairs(const uint32_t (&T)[4], uint32_
   }
 }
 
-// The eight lookups of entry words JA, JA + 1 of word j (JO = j mod 2) are the chunks 8 JO + 2 JA .. + 3 of the
-// tile's half j / 2, whose activations x holds.  Last lookup first: LDS answers in issue order, so one counter
-// wait covers the eight.  Two sets of sums take turns, so that no matrix instruction waits for the one before it.
+// One sample: the eight lookups of entry words JA, JA + 1 are the pairs 4 JA .. 4 JA + 7 of the word, which the
+// lanes JA, JA + 1 of the quad hold in x.  Last lookup first: LDS answers in issue order, so one counter wait
+// covers the eight.
+template <int JA>
+__device__ __forceinline__ void lane_consume_pairs(const uint32_t (&v)[8], const u32x4& x, float (&acc)[4]) {
+  dot2_quad<JA + 1>(acc[3], x.w, v[7]);
+  dot2_quad<JA + 1>(acc[2], x.z, v[6]);
+  dot2_quad<JA + 1>(acc[1], x.y, v[5]);
+  dot2_quad<JA + 1>(acc[0], x.x, v[4]);
+  dot2_quad<JA>(acc[3], x.w, v[3]);
+  dot2_quad<JA>(acc[2], x.z, v[2]);
+  dot2_quad<JA>(acc[1], x.y, v[1]);
+  dot2_quad<JA>(acc[0], x.x, v[0]);
+}
+
+// Four samples: the eight lookups of entry words JA, JA + 1 of word j (JO = j mod 2) are the chunks 8 JO + 2 JA .. + 3 of the
+// tile's half j / 2, whose activations x holds.
 template <int JA, int JO>
 __device__ __forceinline__ void lane_consume_pairs(const uint32_t (&v)[8], uint64_t x, f32x4 (&acc)[2]) {
   mfma_chunk<8 * JO + 2 * JA + 3>(acc[1], x, v[6], v[7]);
@@ -236,8 +278,17 @@ __device__ __forceinline__ void lane_issue_singles(const uint32_t (&R)[8], uint3
 #undef DPLLM_LANE_LOOKUP
 }
 
-// a table entry is an fp16 in the low half of a dword: two of them pack into one fp16 pair; columns 8 JJ .. + 7 of
-// word j (JO = j mod 2) are the chunks 8 JO + 2 JJ, + 1
+// a table entry is an fp16 in the low half of a dword: two of them pack into one fp16 pair.  One sample: columns
+// 8 JJ .. + 7 of the word are the pairs lane JJ of the quad holds
+template <int JJ>
+__device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], const u32x4& x, float (&acc)[4]) {
+  dot2_quad<JJ>(acc[3], x.w, v[6] | (v[7] << 16));
+  dot2_quad<JJ>(acc[2], x.z, v[4] | (v[5] << 16));
+  dot2_quad<JJ>(acc[1], x.y, v[2] | (v[3] << 16));
+  dot2_quad<JJ>(acc[0], x.x, v[0] | (v[1] << 16));
+}
+
+// four samples: columns 8 JJ .. + 7 of word j (JO = j mod 2) are the chunks 8 JO + 2 JJ, + 1
 template <int JJ, int JO>
 __device__ __forceinline__ void lane_consume_singles(const uint32_t (&v)[8], uint64_t x, f32x4 (&acc)[2]) {
   mfma_chunk<8 * JO + 2 * JJ + 1>(acc[1], x, v[4] | (v[5] << 16), v[6] | (v[7] << 16));
@@ -254,13 +305,51 @@ __device__ __forceinline__ void lane_merge_fields(const uint32_t (&w)[K], uint32
 
 // ---- one tile -------------------------------------------------------------------------------------------------
 // Lookups run in chunks of eight; the next chunk's lookups are issued before the current chunk's multiply-adds.
-// xmine: where this lane finds its chunk of the parked activations of the tile's first half (its sample's slot +
-// 8 * (lane / 4)); the chunk of the second half is 128 bytes on
+// xmine: where this lane finds its part of the tile's parked activations.  One sample: the 16 bytes of its quad
+// lane in word 0 (slot + 16 * (lane mod 4)), those of word j 64 j bytes on.  Four samples: its chunk of the tile's
+// first half (its sample's slot + 8 * (lane / 4)), that of the second half 128 bytes on.
+template <int K, int NB>
+struct LaneX;
+template <int K>
+struct LaneX<K, 1> {
+  u32x4 q[4];   // q[j][m] = pair 4 (lane mod 4) + m of word j
+  __device__ __forceinline__ void load(const char* xmine) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) q[j] = *reinterpret_cast<const u32x4*>(xmine + j * 64);
+  }
+};
+template <int K>
+struct LaneX<K, 4> {
+  uint64_t a[2];   // a[h] = chunk 16 h + lane / 4 of the tile, of sample lane mod 4
+  __device__ __forceinline__ void load(const char* xmine) {
+    a[0] = *reinterpret_cast<const uint64_t*>(xmine);
+    a[1] = *reinterpret_cast<const uint64_t*>(xmine + 128);
+  }
+};
+
+template <int JA, int J, int K>
+__device__ __forceinline__ void lane_mac_pairs(const uint32_t (&v)[8], const LaneX<K, 1>& x, LaneAcc<1>& acc) {
+  lane_consume_pairs<JA>(v, x.q[J], acc.v);
+}
+template <int JA, int J, int K>
+__device__ __forceinline__ void lane_mac_pairs(const uint32_t (&v)[8], const LaneX<K, 4>& x, LaneAcc<4>& acc) {
+  lane_consume_pairs<JA, J & 1>(v, x.a[J >> 1], acc.v);
+}
+template <int JJ, int J, int K>
+__device__ __forceinline__ void lane_mac_singles(const uint32_t (&v)[8], const LaneX<K, 1>& x, LaneAcc<1>& acc) {
+  lane_consume_singles<JJ>(v, x.q[J], acc.v);
+}
+template <int JJ, int J, int K>
+__device__ __forceinline__ void lane_mac_singles(const uint32_t (&v)[8], const LaneX<K, 4>& x, LaneAcc<4>& acc) {
+  lane_consume_singles<JJ, J & 1>(v, x.a[J >> 1], acc.v);
+}
+
 template <int K, int NB>
 __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t lanecol, const char* lds, const char* xmine,
-                                             f32x4 (&acc)[2], uint32_t (&addr)[8], uint32_t mask, const MergeMasks<K>& M) {
+                                             LaneAcc<NB>& acc, uint32_t (&addr)[8], uint32_t mask, const MergeMasks<K>& M) {
   uint32_t va[8], vb[8];
-  const uint64_t xa[2] = {*reinterpret_cast<const uint64_t*>(xmine), *reinterpret_cast<const uint64_t*>(xmine + 128)};
+  LaneX<K, NB> x;
+  x.load(xmine);
   using J0 = std::integral_constant<int, 0>;
   using J1 = std::integral_constant<int, 1>;
   using J2 = std::integral_constant<int, 2>;
@@ -281,11 +370,11 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t 
       constexpr int j = decltype(jc)::value;
       lane_issue_pairs<2, K == 3>(T[j], lanecol, lds, vb, addr, mask);
       sched_fence();
-      lane_consume_pairs<0, j & 1>(va, xa[j >> 1], acc);
+      lane_mac_pairs<0, j>(va, x, acc);
       sched_fence();
       if constexpr (j + 1 < 4) lane_issue_pairs<0, K == 3>(T[j + 1], lanecol, lds, va, addr, mask);
       sched_fence();
-      lane_consume_pairs<2, j & 1>(vb, xa[j >> 1], acc);
+      lane_mac_pairs<2, j>(vb, x, acc);
       sched_fence();
     };
     word(J0{}); word(J1{}); word(J2{}); word(J3{});
@@ -308,19 +397,19 @@ __device__ __forceinline__ void lane_compute(const LaneTile<K, NB>& t, uint32_t 
       }
       lane_issue_singles<K, 1>(R[j & 1], lanecol, lds, vb);
       sched_fence();
-      lane_consume_singles<0, j & 1>(va, xa[j >> 1], acc);
+      lane_mac_singles<0, j>(va, x, acc);
       sched_fence();
       lane_issue_singles<K, 2>(R[j & 1], lanecol, lds, va);
       sched_fence();
-      lane_consume_singles<1, j & 1>(vb, xa[j >> 1], acc);
+      lane_mac_singles<1, j>(vb, x, acc);
       sched_fence();
       lane_issue_singles<K, 3>(R[j & 1], lanecol, lds, vb);
       sched_fence();
-      lane_consume_singles<2, j & 1>(va, xa[j >> 1], acc);
+      lane_mac_singles<2, j>(va, x, acc);
       sched_fence();
       if constexpr (j + 1 < 4) lane_issue_singles<K, 0>(R[(j + 1) & 1], lanecol, lds, va);
       sched_fence();
-      lane_consume_singles<3, j & 1>(vb, xa[j >> 1], acc);
+      lane_mac_singles<3, j>(vb, x, acc);
       sched_fence();
     };
     word(J0{}); word(J1{}); word(J2{}); word(J3{});
@@ -438,8 +527,8 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   constexpr bool kEarlyX = K != 4;
   const bool keep = NB == 1 && c1 - c0 <= kLaneKeepTiles;
   char* kept = ready + 256;
-  // this lane's view of the parked activations: its sample's slot (lane mod 4, with several samples), its quad's chunk
-  const int xlane = (NB == 1 ? 0 : (lane & 3) * 256) + (lane >> 2) * 8;
+  // this lane's view of a tile's parked activations (see lane_compute)
+  const int xlane = NB == 1 ? (lane & 3) * 16 : (lane & 3) * 256 + (lane >> 2) * 8;
   uint32_t xkeep[kLaneKeepTiles];
   if (keep) {
     if constexpr (kEarlyX) {
@@ -469,8 +558,8 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
     for (int i = 0; i < kLaneKeepTiles; ++i)
       if (c0 + i < c1) lane_park_x<K>(lane_mask_x(job, c0 + i, lane, xkeep[i]), lane, repair, kept + i * 256);
   }
-  f32x4 acc[2];   // two sets that take turns; [i] = the sum of sample i (one sample: four equal sums)
-  acc[0] = acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  LaneAcc<NB> acc;
+  acc.zero();
   MergeMasks<K> M;
   if constexpr (K <= 6) M.init();
   uint32_t addr[8], mask = 0x3fu;              // k = 3: address registers of the lookups (see lane_issue_pairs)
@@ -485,8 +574,8 @@ __device__ __forceinline__ void gemv_lane(const GemvJob& job, uint32_t lut_off, 
   };
   auto close_block = [&]() {
 #pragma unroll
-    for (int b = 0; b < NB; ++b) red[(b * kLaneWaves + wave) * 64 + lane] = acc[0][b] + acc[1][b];
-    acc[0] = acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < NB; ++b) red[(b * kLaneWaves + wave) * 64 + lane] = acc.sum(b);
+    acc.zero();
     lane_group_barrier();
     const bool storer = wave < NB && (NB == 1 || wave < job.nsamples);   // wavefront b stores sample b
     float s = 0.f;
