@@ -209,6 +209,11 @@ int dpllm_decode_step_parts(dpllm_model* m, const void* const* xs, void* const* 
  * from the private device layout, to idx_dev (device).  Errors: EINVAL, ERANGE, ESTATE, EHIP. */
 int dpllm_debug_unpack(dpllm_model* m, int id, int k, uint8_t* idx_dev, void* stream);
 
+/* Parity aid (host only, touches no device): where the private device layout keeps the plane-`plane` bit of the
+ * weight (row, col) of a linear of this shape: *byte_offset from the start of the arena (a multiple of 4: the
+ * 32-bit word), *bit inside that word.  Errors: EINVAL, ESHAPE, ERANGE. */
+int dpllm_debug_locate(int out, int in, int p, int kmin, int plane, int row, int col, size_t* byte_offset, int* bit);
+
 /* Measurement aid: a plain 128-bit copy kernel, bytes % 16 == 0, both pointers device and 16-byte
  * aligned.  Its known traffic (bytes read + bytes written) scales the HBM byte counters that the
  * profiles report for the GEMV.  Errors: EINVAL, EHIP. */

@@ -22,7 +22,8 @@ SYMBOLS = ["dpllm_model_create", "dpllm_model_destroy", "dpllm_last_error", "dpl
            "dpllm_workspace_bytes", "dpllm_set_workspace",
            "dpllm_load_linear", "dpllm_set_selector", "dpllm_set_threshold", "dpllm_set_active_pair",
            "dpllm_set_target_entry", "dpllm_set_target", "dpllm_set_selector_input",
-           "dpllm_estimate", "dpllm_estimate_noalloc", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_copy", "dpllm_debug_read"]
+           "dpllm_estimate", "dpllm_estimate_noalloc", "dpllm_gemv", "dpllm_decode_step", "dpllm_decode_step_parts", "dpllm_debug_unpack", "dpllm_debug_locate",
+           "dpllm_debug_copy", "dpllm_debug_read"]
 
 
 class DpllmError(RuntimeError):
@@ -43,6 +44,7 @@ def _load():
     L.dpllm_last_error.argtypes = [vp]
     L.dpllm_last_error.restype = C.c_char_p
     L.dpllm_linear_device_bytes.argtypes = [i32, i32, i32, i32, C.POINTER(sz)]
+    L.dpllm_debug_locate.argtypes = [i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(i32)]
     L.dpllm_load_linear.argtypes = [vp, i32, i32, i32, i32, i32, vp, C.POINTER(vp), i32, vp, sz, vp]
     L.dpllm_set_selector.argtypes = [vp, i32, i32, i32, i32, vp, i32, f32, f32, f32]
     L.dpllm_set_threshold.argtypes = [vp, i32, i32, i32, f32]

@@ -638,6 +638,19 @@ int dpllm_linear_device_bytes(int out, int in, int p, int kmin, size_t* bytes) {
   return DPLLM_OK;
 }
 
+int dpllm_debug_locate(int out, int in, int p, int kmin, int plane, int row, int col, size_t* byte_offset, int* bit) {
+  if (!byte_offset || !bit) return DPLLM_EINVAL;
+  int rc = check_shape(out, in, p, kmin);
+  if (rc != DPLLM_OK) return rc;
+  if (plane < 0 || plane >= p || row < 0 || row >= out || col < 0 || col >= in) return DPLLM_ERANGE;
+  const LinearLayout L = LinearLayout::make(out, in, p, kmin);
+  // the word of the tile, the column's position inside it, and the rotation of plane b (see layout_device.hpp)
+  const size_t word = plane_word_index(row, col / 32, L.ncc);
+  *byte_offset = (size_t)plane * L.plane_bytes + word * 4;
+  *bit = ((col_to_pos(col % 32) - plane) % 32 + 32) % 32;
+  return DPLLM_OK;
+}
+
 int dpllm_workspace_bytes(const dpllm_model* m, size_t* bytes) {
   if (!m || !bytes) return DPLLM_EINVAL;
   *bytes = carve_workspace(m).total;

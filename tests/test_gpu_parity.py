@@ -531,6 +531,35 @@ def test_target_switch_between_graph_replays(dp):
     model.close()
 
 
+def test_loaded_planes_sit_where_the_host_says(dp):
+    """dpllm_debug_locate (host arithmetic, pinned without a GPU in test_abi_symbols.py) against what
+    dpllm_load_linear really writes: planes with a few single bits set, loaded, and the arena read back: exactly
+    the predicted bits of the plane regions are set, ragged rows and columns included."""
+    import ctypes as C
+    out, in_, p = 70, 288, 5
+    rng = np.random.default_rng(5)
+    planes = np.zeros((p, out, in_ // 32), dtype=np.uint32)
+    picks = {(int(rng.integers(p)), int(rng.integers(out)), int(rng.integers(in_))) for _ in range(60)}
+    picks |= {(0, 0, 0), (p - 1, out - 1, in_ - 1), (2, 63, 127), (3, 64, 128)}
+    for b, o, c in picks:
+        planes[b, o, c // 32] |= np.uint32(1) << np.uint32(c % 32)
+    luts = {k: np.zeros((out, 1 << k), dtype=np.uint16) for k in range(3, p + 1)}
+    model = dp.Model(1)
+    model.dpllm_load_linear(0, planes, luts, 3)
+    torch.cuda.synchronize()
+    arena = model.arenas[0].cpu().numpy()
+    nrq, ncc = (out + 63) // 64, (in_ // 32 + 3) // 4
+    words = arena[:p * nrq * ncc * 1024].view(np.uint32)
+    want = np.zeros_like(words)
+    for b, o, c in picks:
+        off, bit = C.c_size_t(0), C.c_int(0)
+        assert dp.lib.dpllm_debug_locate(out, in_, p, 3, b, o, c, C.byref(off), C.byref(bit)) == dp.DPLLM_OK
+        want[off.value // 4] |= np.uint32(1) << np.uint32(bit.value)
+    assert int(np.unpackbits(want.view(np.uint8)).sum()) == len(picks)
+    assert np.array_equal(words, want)
+    model.close()
+
+
 # ----------------------------------------------------------------------------- T7 error paths
 def test_abi_error_paths(dp):
     lin = synth.make_linear(8, 64, 4, 3, seed=1)
