@@ -110,3 +110,12 @@ def test_device_layout_is_a_permutation_with_the_stated_structure(lib, out, in_,
     assert f(out, in_, p, 3, 0, out, 0, C.byref(off), C.byref(bit)) == -3
     assert f(out, in_, p, 3, 0, 0, in_, C.byref(off), C.byref(bit)) == -3
     assert f(out, in_, p, 3, 0, 0, 0, None, C.byref(bit)) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits with an error before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
